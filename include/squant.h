@@ -1,0 +1,105 @@
+/* SQuant weight-quantization solver for AMD MI355X (gfx950) -- C ABI.
+ *
+ * Implements the progressive CASE-flipping solver of "SQuant: On-the-Fly Data-Free
+ * Quantization via Diagonal Hessian Approximation" (ICLR 2022), Section 3.3-3.4:
+ * Algorithm 1 (progressive SQuant), Algorithm 2 (SQuantFlip) and Algorithm 3
+ * (perturbation update, Appendix B.3), preceded by the per-output-channel
+ * quantization range of Section 4 (symmetric absmax scale) and the
+ * scale/clip/round formula of Section 2.2.
+ *
+ * A weight tensor is W[cout][cin][kh][kw], contiguous, row-major, binary32
+ * (Section 2.1: M = cout output channels, N = cin "kernels" per output channel,
+ * K = kh*kw elements per kernel; a fully connected layer is kh = kw = 1; for a
+ * grouped / depthwise convolution cin is the per-group input channel count).
+ *
+ * For every output channel m:
+ *   scales[m] = max|W[m]| / qmax,  qmax = 2^(bits-1) - 1   (1.0f if the channel is all zero)
+ *   x = W / scales[m] (one IEEE division), clamped to [-qmax, qmax]
+ *   SQuant-E : code = round-half-even(x), perturbation p = code - x      (Eq. 5)
+ *   SQuant-K : per kernel, flip the k = round(|sum p|) same-sign elements with
+ *              the largest |p| one step against the sum                 (Eq. 6, Alg. 2)
+ *   update   : per kernel, keep one flip candidate                      (Alg. 3)
+ *   SQuant-C : per channel, flip the candidate of the k_c = round(|sum p|)
+ *              same-sign kernels with the largest candidate |p|         (Eq. 7, Alg. 2)
+ * Perturbations are held in Q24 fixed point and summed as integers, an exact half
+ * in round(|sum|) takes the fewer flips, and ties in a top-k go to the lowest
+ * index, so the result does not depend on launch geometry and is reproducible
+ * bit for bit.
+ *
+ * Conventions for every entry point
+ *   - pointers named d_* are DEVICE pointers (HIP), h_* are HOST pointers;
+ *   - the caller owns every buffer; the library keeps no state between calls and
+ *     allocates no device memory;
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream); calls
+ *     enqueue work and return; outputs are valid once the stream has been synchronised;
+ *   - codes must not alias the weights; inputs must be finite (NaN/Inf: memory
+ *     safe, result unspecified);
+ *   - arguments are checked on the host before anything is launched and an
+ *     integer status is returned (never an exception or abort).
+ */
+#ifndef SQUANT_H_
+#define SQUANT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Which stages run (Section 4.3 ablation names E, E&K, E&K&C, E&C). */
+typedef enum {
+  SQUANT_MODE_E = 0,   /* rounding only */
+  SQUANT_MODE_EK = 1,  /* + kernel-wise flip */
+  SQUANT_MODE_EKC = 2, /* + output-channel-wise flip (the full method) */
+  SQUANT_MODE_EC = 3   /* channel-wise flip on the rounded weights, no kernel-wise flip */
+} squant_mode_t;
+
+typedef enum {
+  SQUANT_OK = 0,
+  SQUANT_ERR_NULL = 1,      /* a required pointer is NULL */
+  SQUANT_ERR_SHAPE = 2,     /* a dimension is <= 0, or the sizes overflow */
+  SQUANT_ERR_BITS = 3,      /* bits outside [2, 8] */
+  SQUANT_ERR_MODE = 4,      /* unknown mode */
+  SQUANT_ERR_WORKSPACE = 5, /* workspace missing or too small */
+  SQUANT_ERR_DEVICE = 6,    /* a HIP call failed */
+  SQUANT_ERR_UNSUPPORTED = 7 /* one output channel (cin*kh*kw) exceeds what one workgroup's LDS holds */
+} squant_status_t;
+
+/* One weight tensor of a batched call. */
+typedef struct {
+  const float* w;            /* in : device, cout*cin*kh*kw binary32 */
+  int8_t* codes;             /* out: device, same element count and layout, values in [-qmax, qmax] */
+  float* scales;             /* out: device, cout binary32 */
+  int32_t cout, cin, kh, kw;
+} squant_tensor_t;
+
+/* Quantize one tensor (Algorithm 1 over all output channels).
+ * d_w [cout*cin*kh*kw] in, d_codes [same count] out, d_scales [cout] out. */
+int squant_quantize(const float* d_w, int32_t cout, int32_t cin, int32_t kh, int32_t kw,
+                    int32_t bits, squant_mode_t mode, int8_t* d_codes, float* d_scales,
+                    void* stream);
+
+/* Device bytes squant_quantize_batched needs for its descriptor table. */
+size_t squant_batched_workspace_bytes(int32_t n_tensors);
+
+/* Quantize a set of tensors (the layers of a network are independent, Section 4.2)
+ * with one launch per kernel variant present instead of one per tensor.
+ * h_tensors: HOST array of n_tensors descriptors holding DEVICE pointers; it may be
+ * freed or reused as soon as the call returns.  d_workspace: caller-allocated device
+ * memory of at least squant_batched_workspace_bytes(n_tensors), 16-byte aligned; it must
+ * stay untouched until the stream has passed this call.  n_tensors = 0 is a no-op. */
+int squant_quantize_batched(const squant_tensor_t* h_tensors, int32_t n_tensors, int32_t bits,
+                            squant_mode_t mode, void* d_workspace, size_t workspace_bytes,
+                            void* stream);
+
+/* Largest cin*kh*kw one output channel may have (device dependent; 0 on error). */
+int64_t squant_max_channel_elems(int32_t kh, int32_t kw);
+
+const char* squant_status_string(int status);
+int squant_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SQUANT_H_ */

@@ -1,0 +1,104 @@
+"""ctypes access to the CPU reference solver (test infrastructure only).
+
+Only the test-suite, the smoke check and the benchmark's CPU-baseline leg may
+import this package; the GPU product path never does.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "squant_oracle.cpp")
+_LIB = os.path.join(_HERE, "libsquant_oracle.so")
+
+MODE_E, MODE_EK, MODE_EKC, MODE_EC = 0, 1, 2, 3
+ONE = 1 << 24
+HALF = 1 << 23
+
+CXXFLAGS = ["-std=c++17", "-O2", "-fno-fast-math", "-ffp-contract=off", "-shared", "-fPIC",
+            "-pthread"]
+
+
+def build(force: bool = True) -> str:
+    if force or not os.path.exists(_LIB):
+        subprocess.check_call(["g++", *CXXFLAGS, _SRC, "-o", _LIB])
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB):
+            build()
+        L = ctypes.CDLL(_LIB)
+        i32, vp = ctypes.c_int32, ctypes.c_void_p
+        L.squant_oracle_quantize.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp]
+        L.squant_oracle_quantize_mt.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp, i32]
+        L.squant_oracle_quantize_trace.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp] + [vp] * 7
+        for f in (L.squant_oracle_quantize, L.squant_oracle_quantize_mt,
+                  L.squant_oracle_quantize_trace, L.squant_oracle_hardware_threads):
+            f.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _prep(w):
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    if w.ndim == 2:
+        w = w[:, :, None, None]
+    if w.ndim == 3:
+        w = w[:, :, :, None]
+    assert w.ndim == 4
+    return w
+
+
+def quantize(w, bits: int, mode: int = MODE_EKC, threads: int = 1):
+    """Returns (codes int8 [same shape as w], scales float32 [cout])."""
+    w4 = _prep(w)
+    cout, cin, kh, kw = w4.shape
+    codes = np.empty(w4.shape, dtype=np.int8)
+    scales = np.empty(cout, dtype=np.float32)
+    if threads > 1:
+        rc = lib().squant_oracle_quantize_mt(w4.ctypes.data, cout, cin, kh, kw, bits, mode,
+                                             codes.ctypes.data, scales.ctypes.data, threads)
+    else:
+        rc = lib().squant_oracle_quantize(w4.ctypes.data, cout, cin, kh, kw, bits, mode,
+                                          codes.ctypes.data, scales.ctypes.data)
+    if rc != 0:
+        raise ValueError(f"squant_oracle_quantize failed with status {rc}")
+    return codes, scales
+
+
+def quantize_trace(w, bits: int, mode: int = MODE_EKC):
+    """Returns (codes, scales, trace dict of the intermediate decisions, Q24 integers)."""
+    w4 = _prep(w)
+    cout, cin, kh, kw = w4.shape
+    codes = np.empty(w4.shape, dtype=np.int8)
+    scales = np.empty(cout, dtype=np.float32)
+    tr = {
+        "kernel_k": np.empty((cout, cin), np.int32),
+        "kernel_sum": np.empty((cout, cin), np.int32),
+        "cand_index": np.empty((cout, cin), np.int32),
+        "cand_value": np.empty((cout, cin), np.int32),
+        "channel_sum": np.empty(cout, np.int64),
+        "channel_k": np.empty(cout, np.int32),
+        "perturbation": np.empty((cout, cin, kh * kw), np.int32),
+    }
+    rc = lib().squant_oracle_quantize_trace(
+        w4.ctypes.data, cout, cin, kh, kw, bits, mode, codes.ctypes.data, scales.ctypes.data,
+        *[tr[k].ctypes.data for k in ("kernel_k", "kernel_sum", "cand_index", "cand_value",
+                                      "channel_sum", "channel_k", "perturbation")])
+    if rc != 0:
+        raise ValueError(f"squant_oracle_quantize_trace failed with status {rc}")
+    return codes, scales, tr
+
+
+def hardware_threads() -> int:
+    return int(lib().squant_oracle_hardware_threads())
