@@ -1,0 +1,150 @@
+"""Thin ctypes binding of libsquant_hip.so: argument marshalling only.
+
+Every step of the solver runs in the HIP kernels; torch is used for device
+memory and streams.  There is no CPU fallback: a missing library is an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Iterable, List, Sequence, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsquant_hip.so")
+
+MODE_E, MODE_EK, MODE_EKC, MODE_EC = 0, 1, 2, 3
+MODES = {"E": MODE_E, "EK": MODE_EK, "EKC": MODE_EKC, "EC": MODE_EC}
+
+
+class squant_tensor_t(ctypes.Structure):
+    _fields_ = [("w", ctypes.c_void_p), ("codes", ctypes.c_void_p), ("scales", ctypes.c_void_p),
+                ("cout", ctypes.c_int32), ("cin", ctypes.c_int32), ("kh", ctypes.c_int32),
+                ("kw", ctypes.c_int32)]
+
+
+class SQuantError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"squant status {status}: {text}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib():
+    """Loads the in-tree HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; "
+                "g.build()'); there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        i32, vp, sz = ctypes.c_int32, ctypes.c_void_p, ctypes.c_size_t
+        L.squant_quantize.argtypes = [vp, i32, i32, i32, i32, i32, ctypes.c_int, vp, vp, vp]
+        L.squant_quantize.restype = ctypes.c_int
+        L.squant_batched_workspace_bytes.argtypes = [i32]
+        L.squant_batched_workspace_bytes.restype = sz
+        L.squant_quantize_batched.argtypes = [ctypes.POINTER(squant_tensor_t), i32, i32,
+                                              ctypes.c_int, vp, sz, vp]
+        L.squant_quantize_batched.restype = ctypes.c_int
+        L.squant_max_channel_elems.argtypes = [i32, i32]
+        L.squant_max_channel_elems.restype = ctypes.c_int64
+        L.squant_status_string.argtypes = [ctypes.c_int]
+        L.squant_status_string.restype = ctypes.c_char_p
+        L.squant_version.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def squant_status_string(status: int) -> str:
+    return lib().squant_status_string(status).decode()
+
+
+def squant_version() -> int:
+    return int(lib().squant_version())
+
+
+def squant_max_channel_elems(kh: int, kw: int) -> int:
+    return int(lib().squant_max_channel_elems(kh, kw))
+
+
+def squant_batched_workspace_bytes(n_tensors: int) -> int:
+    return int(lib().squant_batched_workspace_bytes(n_tensors))
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise SQuantError(rc, squant_status_string(rc))
+
+
+def _shape4(w: torch.Tensor) -> Tuple[int, int, int, int]:
+    if w.dim() == 2:
+        return (w.shape[0], w.shape[1], 1, 1)
+    if w.dim() == 4:
+        return tuple(w.shape)  # type: ignore[return-value]
+    raise ValueError("weight must be [cout, cin] or [cout, cin, kh, kw]")
+
+
+def _stream_ptr(stream) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+def _check_weight(w: torch.Tensor):
+    if not (w.is_cuda and w.dtype == torch.float32 and w.is_contiguous()):
+        raise ValueError("weight must be a contiguous float32 tensor in device memory")
+
+
+def squant_quantize(w: torch.Tensor, bits: int, mode: int = MODE_EKC, codes: torch.Tensor = None,
+                    scales: torch.Tensor = None, stream=None):
+    """Quantize one weight tensor; returns (codes int8 like w, scales float32 [cout]).
+
+    Asynchronous on `stream` (default: torch's current stream)."""
+    _check_weight(w)
+    cout, cin, kh, kw = _shape4(w)
+    if codes is None:
+        codes = torch.empty(w.shape, dtype=torch.int8, device=w.device)
+    if scales is None:
+        scales = torch.empty(cout, dtype=torch.float32, device=w.device)
+    _check(lib().squant_quantize(w.data_ptr(), cout, cin, kh, kw, bits, mode, codes.data_ptr(),
+                                 scales.data_ptr(), _stream_ptr(stream)))
+    return codes, scales
+
+
+class BatchPlan:
+    """Descriptor array + workspace + outputs of a batched call, built once and reusable."""
+
+    def __init__(self, weights: Sequence[torch.Tensor]):
+        self.weights = list(weights)
+        n = len(self.weights)
+        dev = self.weights[0].device if n else torch.device("cuda")
+        self.codes: List[torch.Tensor] = []
+        self.scales: List[torch.Tensor] = []
+        self.desc = (squant_tensor_t * max(n, 1))()
+        for i, w in enumerate(self.weights):
+            _check_weight(w)
+            cout, cin, kh, kw = _shape4(w)
+            c = torch.empty(w.shape, dtype=torch.int8, device=dev)
+            s = torch.empty(cout, dtype=torch.float32, device=dev)
+            self.codes.append(c)
+            self.scales.append(s)
+            self.desc[i] = squant_tensor_t(w.data_ptr(), c.data_ptr(), s.data_ptr(), cout, cin, kh, kw)
+        self.n = n
+        self.ws_bytes = squant_batched_workspace_bytes(n)
+        self.workspace = torch.empty(max(self.ws_bytes, 16), dtype=torch.uint8, device=dev)
+
+    def run(self, bits: int, mode: int = MODE_EKC, stream=None):
+        _check(lib().squant_quantize_batched(self.desc, self.n, bits, mode,
+                                             self.workspace.data_ptr(), self.ws_bytes,
+                                             _stream_ptr(stream)))
+        return self.codes, self.scales
+
+
+def squant_quantize_batched(weights: Iterable[torch.Tensor], bits: int, mode: int = MODE_EKC,
+                            stream=None):
+    """Quantize a set of weight tensors in one call; returns (list of codes, list of scales)."""
+    plan = BatchPlan(list(weights))
+    return plan.run(bits, mode, stream)

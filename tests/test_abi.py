@@ -1,0 +1,90 @@
+"""Host-side checks that need no GPU: the library loads, exports what the header declares,
+and rejects bad arguments before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2202_07471_amd", "libsquant_hip.so")
+HEADER = os.path.join(ROOT, "include", "squant.h")
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(LIB):
+        import __graft_entry__
+        __graft_entry__.build()
+    from paper_2202_07471_amd import binding
+    return binding.lib()
+
+
+def declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(squant_[a-z_0-9]+)\s*\(", src)))
+
+
+def test_header_symbols_are_exported(L):
+    names = declared_functions()
+    assert {"squant_quantize", "squant_quantize_batched", "squant_batched_workspace_bytes",
+            "squant_status_string", "squant_version"} <= set(names)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_status_strings(L):
+    seen = set()
+    for s in range(0, 8):
+        txt = L.squant_status_string(s).decode()
+        assert txt and txt not in seen
+        seen.add(txt)
+    assert L.squant_status_string(99).decode() == "unknown status"
+    assert L.squant_version() >= 100
+
+
+def test_bad_arguments_are_rejected_on_the_host(L):
+    p = ctypes.c_void_p(0x1000)   # never dereferenced: validation precedes any launch
+    q = lambda *a: L.squant_quantize(*a)
+    assert q(None, 4, 4, 3, 3, 4, 2, p, p, None) == 1
+    assert q(p, 4, 4, 3, 3, 4, 2, None, p, None) == 1
+    assert q(p, 4, 4, 3, 3, 4, 2, p, None, None) == 1
+    assert q(p, 0, 4, 3, 3, 4, 2, p, p, None) == 2
+    assert q(p, 4, -1, 3, 3, 4, 2, p, p, None) == 2
+    assert q(p, 4, 4, 0, 3, 4, 2, p, p, None) == 2
+    assert q(p, 4, 1 << 20, 1 << 10, 1 << 10, 4, 2, p, p, None) == 2
+    assert q(p, 4, 4, 3, 3, 1, 2, p, p, None) == 3
+    assert q(p, 4, 4, 3, 3, 9, 2, p, p, None) == 3
+    assert q(p, 4, 4, 3, 3, 4, 4, p, p, None) == 4
+    assert q(p, 4, 4, 3, 3, 4, -1, p, p, None) == 4
+
+
+def test_batched_argument_checks(L):
+    from paper_2202_07471_amd.binding import squant_tensor_t
+    assert L.squant_batched_workspace_bytes(0) == 0
+    assert L.squant_batched_workspace_bytes(3) >= 3 * 40
+    arr = (squant_tensor_t * 2)()
+    arr[0] = squant_tensor_t(0x1000, 0x2000, 0x3000, 4, 4, 3, 3)
+    arr[1] = squant_tensor_t(0x1000, 0x2000, 0x3000, 4, 4, 1, 1)
+    ws = ctypes.c_void_p(0x4000)
+    assert L.squant_quantize_batched(arr, 0, 4, 2, None, 0, None) == 0      # empty batch
+    assert L.squant_quantize_batched(None, 2, 4, 2, ws, 1024, None) == 1
+    assert L.squant_quantize_batched(arr, -1, 4, 2, ws, 1024, None) == 2
+    assert L.squant_quantize_batched(arr, 2, 10, 2, ws, 1024, None) == 3
+    assert L.squant_quantize_batched(arr, 2, 4, 9, ws, 1024, None) == 4
+    assert L.squant_quantize_batched(arr, 2, 4, 2, None, 1024, None) == 5
+    assert L.squant_quantize_batched(arr, 2, 4, 2, ws, 8, None) == 5
+    assert L.squant_quantize_batched(arr, 2, 4, 2, ctypes.c_void_p(0x4004), 1024, None) == 5
+    arr[1].codes = None
+    assert L.squant_quantize_batched(arr, 2, 4, 2, ws, 1024, None) == 1
+    arr[1].codes = 0x2000
+    arr[1].cin = 0
+    assert L.squant_quantize_batched(arr, 2, 4, 2, ws, 1024, None) == 2
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    import paper_2202_07471_amd as sq
+    with pytest.raises(ValueError):
+        sq.squant_quantize(torch.zeros(4, 4, 3, 3), 4)
