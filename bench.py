@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Throughput of the SQuant solver on one MI355X.
+
+A step is one pass of the whole path (absmax scale, SQuant-E, SQuant-K, candidate update,
+SQuant-C, int8 emit) over the whole workload, as ONE batched library call, with the
+weights already resident in HBM.  Prints one JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5|c1|c2|c3|c4] [--bits 4]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+WORKLOADS = {
+    "c1": (1, "1 x [64,64,3,3] He-normal"),
+    "c2": (2, "ResNet-18-shaped layer set (21 tensors), He-normal"),
+    "c3": (3, "ResNet-50-shaped layer set (54 tensors), He-normal + 1% Laplace outliers"),
+    "c4": (4, "MobileNetV2-shaped layer set (53 tensors), He-normal"),
+    "c5": (5, "256 x [512,512,3,3] fp32, N(0,s) / Student-t(3) per tensor, one batched call"),
+}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def load_traffic(kernel_version: int):
+    """HBM bytes per launch measured with rocprofv3 --pmc (see profiles/); None when the
+    kernel has changed since the counters were taken."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            t = json.load(f)
+        if int(t.get("kernel_version", -1)) == kernel_version:
+            return float(t["bytes_per_launch"])
+    except (OSError, ValueError, KeyError):
+        pass
+    return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c5", choices=sorted(WORKLOADS))
+    ap.add_argument("--bits", type=int, default=4)
+    ap.add_argument("--tensors", type=int, default=None, help="truncate the tensor list (debug)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; every output channel is independent, so "
+              "more GPUs would each take a slice of the tensors with no exchange. "
+              "Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_2202_07471_amd as sq
+    from paper_2202_07471_amd import synth
+
+    sq.binding.lib()   # fails loudly when the HIP library has not been built
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    config, desc = WORKLOADS[args.workload]
+    specs = synth.config_specs(config, n_tensors=args.tensors)
+    n_params = sum(s.numel for s in specs)
+    n_channels = sum(s.shape[0] for s in specs)
+    log(f"[bench] workload {args.workload}: {len(specs)} tensors, {n_params} weights, "
+        f"{n_channels} output channels")
+
+    # ---- synthetic weights: generated once on the host, uploaded, a sample kept for the CPU leg
+    cpu_sample_tensors = 64 if config == 5 else len(specs)
+    t0 = time.time()
+    host_sample, dws = [], []
+    for s in specs:
+        w = synth.generate(s)
+        dws.append(torch.from_numpy(w).to(dev))
+        if s.index < cpu_sample_tensors:
+            host_sample.append(w)
+    torch.cuda.synchronize()
+    log(f"[bench] generated + uploaded in {time.time() - t0:.1f} s "
+        f"({sum(s.dist == 'student_t3' for s in specs)} Student-t tensors)")
+
+    plan = sq.BatchPlan(dws)
+    mode = sq.MODE_EKC
+
+    def step():
+        plan.run(args.bits, mode)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    sq.squant_kernel_timer_enable(max(args.steps, 1))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    kernel_ms = [sq.squant_kernel_timer_elapsed_ms(c) for c in range(args.steps)]
+    sq.squant_kernel_timer_enable(0)
+
+    ms_per_step = elapsed * 1e3 / max(args.steps, 1)
+    value = n_params * args.steps / elapsed / 1e9
+    k_avg_ms = float(np.mean(kernel_ms))
+    algo_bytes = 5.0 * n_params + 4.0 * n_channels      # 4 B read + 1 B written per weight, 4 B per scale
+    achieved = algo_bytes / (k_avg_ms * 1e-3) / 1e9
+    traffic = load_traffic(sq.squant_version()) if args.workload == "c5" and args.tensors is None else None
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "kernel": "squant solver kernel(s) of the batched call",
+                "kernel_ms_avg": round(k_avg_ms, 4), "kernel_ms_min": round(float(np.min(kernel_ms)), 4),
+                "algorithmic_bytes_per_launch": algo_bytes}
+    log(f"[bench] {ms_per_step:.4f} ms/step wall, kernel avg {k_avg_ms:.4f} ms -> "
+        f"{value:.1f} Gparams/s, {achieved:.0f} GB/s algorithmic ({100 * achieved / HBM_PEAK_GBS:.1f}% of peak)")
+
+    # ---- CPU baseline: the reference solver as it stands, on this machine's host cores ----
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import oracle
+        cores = oracle.hardware_threads()
+        env_threads = os.environ.get("OMP_NUM_THREADS")
+        threads = min(cores, int(env_threads)) if env_threads and env_threads.isdigit() else cores
+        sample_params = sum(w.size for w in host_sample)
+        t0 = time.perf_counter()
+        ref = [oracle.quantize(w, args.bits, oracle.MODE_EKC, threads=threads) for w in host_sample]
+        cpu_s = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        n1 = max(1, min(4, len(host_sample)))
+        for w in host_sample[:n1]:
+            oracle.quantize(w, args.bits, oracle.MODE_EKC, threads=1)
+        cpu1_s = time.perf_counter() - t0
+        p1 = sum(w.size for w in host_sample[:n1])
+        # the GPU result of the timed configuration, checked against the same reference
+        mism = 0
+        for i, (rc, rs) in enumerate(ref):
+            gc = plan.codes[i].cpu().numpy()
+            gs = plan.scales[i].cpu().numpy()
+            mism += int((gc != rc).sum()) + int((gs.view(np.uint32) != rs.view(np.uint32)).sum())
+        cpu_baseline = {"value": round(sample_params / cpu_s / 1e9, 5), "unit": "Gparams/s",
+                        "cores": threads, "kind": "oracle",
+                        "sample": f"first {len(host_sample)} tensors of the workload "
+                                  f"({sample_params} weights), EKC, {threads} threads over output channels",
+                        "single_thread_value": round(p1 / cpu1_s / 1e9, 5),
+                        "gpu_mismatches_on_sample": mism}
+        log(f"[bench] CPU reference: {sample_params / cpu_s / 1e6:.1f} Mparams/s on {threads} threads, "
+            f"{p1 / cpu1_s / 1e6:.1f} Mparams/s on 1; GPU mismatches on the sample: {mism}")
+        if mism:
+            log("[bench] ERROR: GPU output differs from the CPU reference")
+
+    out = {
+        "metric": "Gparams/s quantized (4-bit, SQuant-EKC) + achieved HBM GB/s vs peak",
+        "value": round(value, 2), "unit": "Gparams/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32 in, Q24 int32 perturbations, int8 out",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {desc}", "bits": args.bits, "mode": "EKC",
+                   "tensors": len(specs), "weights": n_params, "output_channels": n_channels,
+                   "seed": synth.DEFAULT_SEED},
+        "roofline": roofline, "cpu_baseline": cpu_baseline,
+    }
+    print(json.dumps(out), flush=True)
+    return 1 if (cpu_baseline and cpu_baseline["gpu_mismatches_on_sample"]) else 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -28,8 +28,8 @@
  *
  * Conventions for every entry point
  *   - pointers named d_* are DEVICE pointers (HIP), h_* are HOST pointers;
- *   - the caller owns every buffer; the library keeps no state between calls and
- *     allocates no device memory;
+ *   - the caller owns every buffer; the library allocates no device memory and keeps
+ *     no state between calls (the opt-in kernel timer below excepted);
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream); calls
  *     enqueue work and return; outputs are valid once the stream has been synchronised;
  *   - codes must not alias the weights; inputs must be finite (NaN/Inf: memory
@@ -95,6 +95,19 @@ int squant_quantize_batched(const squant_tensor_t* h_tensors, int32_t n_tensors,
 
 /* Largest cin*kh*kw one output channel may have (device dependent; 0 on error). */
 int64_t squant_max_channel_elems(int32_t kh, int32_t kw);
+
+/* Measurement aid (opt-in, per calling thread; the only state the library keeps).
+ * squant_kernel_timer_enable(slots) creates `slots` pairs of HIP events (0 releases them
+ * and switches the timer off).  While it is on, every squant_quantize /
+ * squant_quantize_batched call of this thread records one event on its stream before its
+ * first solver kernel and one after its last (the descriptor upload of a batched call
+ * lies outside the pair); call number c since the enable uses pair c mod slots.
+ * squant_kernel_timer_elapsed_ms(c, h_ms) waits for call c's second event and writes its
+ * elapsed milliseconds to the HOST float *h_ms; SQUANT_ERR_SHAPE if call c was never
+ * timed or its pair has been reused. */
+int squant_kernel_timer_enable(int32_t slots);
+int64_t squant_kernel_timer_calls(void);
+int squant_kernel_timer_elapsed_ms(int64_t call, float* h_ms);
 
 const char* squant_status_string(int status);
 int squant_version(void);

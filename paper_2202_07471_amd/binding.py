@@ -55,6 +55,11 @@ def lib():
         L.squant_status_string.argtypes = [ctypes.c_int]
         L.squant_status_string.restype = ctypes.c_char_p
         L.squant_version.restype = ctypes.c_int
+        L.squant_kernel_timer_enable.argtypes = [i32]
+        L.squant_kernel_timer_enable.restype = ctypes.c_int
+        L.squant_kernel_timer_calls.restype = ctypes.c_int64
+        L.squant_kernel_timer_elapsed_ms.argtypes = [ctypes.c_int64, ctypes.POINTER(ctypes.c_float)]
+        L.squant_kernel_timer_elapsed_ms.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -73,6 +78,20 @@ def squant_max_channel_elems(kh: int, kw: int) -> int:
 
 def squant_batched_workspace_bytes(n_tensors: int) -> int:
     return int(lib().squant_batched_workspace_bytes(n_tensors))
+
+
+def squant_kernel_timer_enable(slots: int) -> None:
+    _check(lib().squant_kernel_timer_enable(slots))
+
+
+def squant_kernel_timer_calls() -> int:
+    return int(lib().squant_kernel_timer_calls())
+
+
+def squant_kernel_timer_elapsed_ms(call: int) -> float:
+    ms = ctypes.c_float(0.0)
+    _check(lib().squant_kernel_timer_elapsed_ms(call, ctypes.byref(ms)))
+    return float(ms.value)
 
 
 def _check(rc: int):
