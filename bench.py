@@ -56,6 +56,8 @@ def main() -> int:
     ap.add_argument("--bits", type=int, default=4)
     ap.add_argument("--tensors", type=int, default=None, help="truncate the tensor list (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference point for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; every output channel is independent, so "
@@ -97,6 +99,12 @@ def main() -> int:
 
     plan = sq.BatchPlan(dws)
     mode = sq.MODE_EKC
+    if args.calibrate_copy:
+        a_ = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        b_ = torch.empty_like(a_)
+        b_.copy_(a_)            # 1 GiB read + 1 GiB written by one elementwise copy kernel
+        torch.cuda.synchronize()
+        del a_, b_
 
     def step():
         plan.run(args.bits, mode)

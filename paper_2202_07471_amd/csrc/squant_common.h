@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include "squant.h"
+#include "squant_arith.h"
 
 namespace squant {
 
@@ -82,6 +83,66 @@ __device__ __forceinline__ int64_t wave_sum(int64_t v) {
 #pragma unroll
   for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off);
   return v;
+}
+
+// ---- DPP reductions (wave64 = 4 rows of 16 lanes) ----
+// After the four steps every lane of a row holds the row's result; the four row
+// results are then read as scalars.  DPP controls: quad_perm [1,0,3,2] = 0xB1,
+// quad_perm [2,3,0,1] = 0x4E, row_half_mirror = 0x141, row_mirror = 0x140.
+template <int CTRL>
+__device__ __forceinline__ int dpp_i32(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, false);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+
+// max over the wave of non-negative floats; uniform result
+__device__ __forceinline__ float wave_max_dpp(float v) {
+  v = fmaxf(v, dpp_f32<0xB1>(v));
+  v = fmaxf(v, dpp_f32<0x4E>(v));
+  v = fmaxf(v, dpp_f32<0x141>(v));
+  v = fmaxf(v, dpp_f32<0x140>(v));
+  const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+  const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+  const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+  const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+  return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
+}
+
+// sum over the wave of int32 values with |v| <= 2^26 (a row of 16 cannot overflow);
+// uniform 64-bit result
+__device__ __forceinline__ int64_t wave_sum_dpp(int32_t v) {
+  v += dpp_i32<0xB1>(v);
+  v += dpp_i32<0x4E>(v);
+  v += dpp_i32<0x141>(v);
+  v += dpp_i32<0x140>(v);
+  return (int64_t)__builtin_amdgcn_readlane(v, 0) + (int64_t)__builtin_amdgcn_readlane(v, 16) +
+         (int64_t)__builtin_amdgcn_readlane(v, 32) + (int64_t)__builtin_amdgcn_readlane(v, 48);
+}
+
+// Workgroup-wide versions: every thread returns the result.  `slot` holds >= 16 entries.
+__device__ __forceinline__ float block_max_dpp(float v, float* slot) {
+  v = wave_max_dpp(v);
+  const int wid = threadIdx.x / kWave, nw = (blockDim.x + kWave - 1) / kWave;
+  __syncthreads();
+  if ((threadIdx.x & (kWave - 1)) == 0) slot[wid] = v;
+  __syncthreads();
+  float r = slot[0];
+  for (int i = 1; i < nw; ++i) r = fmaxf(r, slot[i]);
+  return r;
+}
+
+__device__ __forceinline__ int64_t block_sum_dpp(int32_t v, int64_t* slot) {
+  const int64_t w = wave_sum_dpp(v);
+  const int wid = threadIdx.x / kWave, nw = (blockDim.x + kWave - 1) / kWave;
+  __syncthreads();
+  if ((threadIdx.x & (kWave - 1)) == 0) slot[wid] = w;
+  __syncthreads();
+  int64_t r = slot[0];
+  for (int i = 1; i < nw; ++i) r += slot[i];
+  return r;
 }
 
 // Every thread returns the block-wide result.  `slot` holds >= 16 entries.

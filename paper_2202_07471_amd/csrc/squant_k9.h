@@ -48,44 +48,22 @@ struct K9Shared {
   SelectShared sel;
 };
 
-// compare-exchange: afterwards a >= b
-#define SQ_CE(a, b)                                  \
-  {                                                  \
-    const int32_t hi_ = max(s[a], s[b]);             \
-    const int32_t lo_ = min(s[a], s[b]);             \
-    s[a] = hi_;                                      \
-    s[b] = lo_;                                      \
-  }
-
-// Leaves the five largest of s[0..8] in s[0] >= s[1] >= ... >= s[4].  A 25-exchange
-// sorting network for nine inputs with the three exchanges that only order the four
-// smallest outputs removed; checked exhaustively on all 0/1 inputs by the test-suite.
-__device__ __forceinline__ void top5_of_9(int32_t (&s)[9]) {
-  SQ_CE(0, 3) SQ_CE(1, 7) SQ_CE(2, 5) SQ_CE(4, 8)
-  SQ_CE(0, 7) SQ_CE(2, 4) SQ_CE(3, 8) SQ_CE(5, 6)
-  SQ_CE(0, 2) SQ_CE(1, 3) SQ_CE(4, 5) SQ_CE(7, 8)
-  SQ_CE(1, 4) SQ_CE(3, 6) SQ_CE(5, 7)
-  SQ_CE(0, 1) SQ_CE(2, 4) SQ_CE(3, 5)
-  SQ_CE(2, 3) SQ_CE(4, 5)
-  SQ_CE(1, 2) SQ_CE(3, 4)
-}
-#undef SQ_CE
-
 // SQuant-E, SQuant-K and the candidate update for kernel Q (0..3) of a thread.
 //   w       the thread's 36 weights; this kernel's are w[9Q .. 9Q+8]
 //   packed  the thread's 36 output bytes as 9 dwords, biased codes (code + 128)
 //   esum    += the kernel's Q24 perturbation sum after SQuant-K
 //   cand_v  Q24 perturbation of the kernel's SQuant-C candidate (0 = none)
 //   cand_b  its byte offset inside the thread's 36 output bytes
-template <int Q>
-__device__ __forceinline__ void k9_kernel_stage(const float (&w)[36], float s, float qmaxf, int mode,
+template <int Q, bool FAST_DIV>
+__device__ __forceinline__ void k9_kernel_stage(const float (&w)[36], float s, float rs, float qmaxf, int mode,
                                                 uint32_t (&packed)[9], int32_t& esum,
                                                 int32_t& cand_v, int& cand_b) {
   float c[9];
   int32_t P[9];
 #pragma unroll
   for (int i = 0; i < 9; ++i) {
-    float x = w[9 * Q + i] / s;  // IEEE binary32 division
+    float x = FAST_DIV ? div_by_reciprocal(w[9 * Q + i], s, rs)
+                       : w[9 * Q + i] / s;  // either way the IEEE binary32 quotient
     x = __builtin_amdgcn_fmed3f(x, -qmaxf, qmaxf);
     c[i] = rintf(x);
     const float p = c[i] - x;  // exact
@@ -201,8 +179,8 @@ __global__ void __launch_bounds__(1024) squant_channel_k9(LaunchArgs a) {
   }
   float amax = 0.0f;
 #pragma unroll
-  for (int j = 0; j < 36; ++j) amax = fmaxf(amax, fabsf(w[j]));
-  amax = block_max(amax, sh.red_f);  // its barriers also retire every read of `stage`
+  for (int j = 0; j < 36; j += 2) amax = fmaxf(fmaxf(amax, fabsf(w[j])), fabsf(w[j + 1]));
+  amax = block_max_dpp(amax, sh.red_f);  // its barriers also retire every read of `stage`
 
   uint32_t* code32 = reinterpret_cast<uint32_t*>(smem);  // the staging area now holds codes
   int8_t* code8 = reinterpret_cast<int8_t*>(smem);
@@ -217,16 +195,24 @@ __global__ void __launch_bounds__(1024) squant_channel_k9(LaunchArgs a) {
     uint32_t packed[9];
 #pragma unroll
     for (int j = 0; j < 9; ++j) packed[j] = 0;
-    k9_kernel_stage<0>(w, s, qmaxf, a.mode, packed, esum, cv[0], cb[0]);
-    k9_kernel_stage<1>(w, s, qmaxf, a.mode, packed, esum, cv[1], cb[1]);
-    k9_kernel_stage<2>(w, s, qmaxf, a.mode, packed, esum, cv[2], cb[2]);
-    k9_kernel_stage<3>(w, s, qmaxf, a.mode, packed, esum, cv[3], cb[3]);
+    if (amax >= 0x1p-60f && amax <= 0x1p60f) {  // uniform over the workgroup
+      const float rs = 1.0f / s;
+      k9_kernel_stage<0, true>(w, s, rs, qmaxf, a.mode, packed, esum, cv[0], cb[0]);
+      k9_kernel_stage<1, true>(w, s, rs, qmaxf, a.mode, packed, esum, cv[1], cb[1]);
+      k9_kernel_stage<2, true>(w, s, rs, qmaxf, a.mode, packed, esum, cv[2], cb[2]);
+      k9_kernel_stage<3, true>(w, s, rs, qmaxf, a.mode, packed, esum, cv[3], cb[3]);
+    } else {
+      k9_kernel_stage<0, false>(w, s, 0.0f, qmaxf, a.mode, packed, esum, cv[0], cb[0]);
+      k9_kernel_stage<1, false>(w, s, 0.0f, qmaxf, a.mode, packed, esum, cv[1], cb[1]);
+      k9_kernel_stage<2, false>(w, s, 0.0f, qmaxf, a.mode, packed, esum, cv[2], cb[2]);
+      k9_kernel_stage<3, false>(w, s, 0.0f, qmaxf, a.mode, packed, esum, cv[3], cb[3]);
+    }
 #pragma unroll
     for (int j = 0; j < 9; ++j) code32[9 * tid + j] = packed[j] ^ 0x80808080u;
   }
   if (a.mode == SQUANT_MODE_EKC || a.mode == SQUANT_MODE_EC) {
     // ---- SQuant-C: every thread of the workgroup takes part ----
-    const int64_t ec = block_sum((int64_t)esum, sh.red_i);  // its barriers publish the codes
+    const int64_t ec = block_sum_dpp(esum, sh.red_i);  // its barriers publish the codes
     const int sgn = sign_of(ec);
     const int64_t kc = flips_for(ec < 0 ? -ec : ec);
     if (kc > 0) {

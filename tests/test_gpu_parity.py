@@ -107,6 +107,26 @@ def test_zero_and_constant_channels(sq):
     assert float(scales[0]) == 1.0 and int(codes[0].abs().max()) == 0
 
 
+@pytest.mark.parametrize("shape", [(24, 64, 3, 3), (24, 96, 1, 1), (24, 10, 2, 2)])
+def test_extreme_magnitudes(sq, shape):
+    """Channels whose absmax sits far outside the usual range (down to subnormal scales, up to
+    near overflow, and just either side of the kernels' internal range switch at 2^-60 / 2^60),
+    with a sprinkling of elements ~2^-110 times smaller than the rest."""
+    rng = np.random.default_rng(99)
+    w = rng.standard_normal(shape).astype(np.float64)
+    tiny = rng.random(shape) < 0.1
+    w[tiny] *= 2.0 ** -110
+    exps = [-140, -127, -120, -100, -61, -60, -59, -30, 0, 30, 59, 60, 61, 100, 120, 125,
+            -62, -58, 58, 62, -90, 90, -10, 10]
+    for m, e in enumerate(exps):
+        w[m] = np.ldexp(w[m], e)
+    w = np.clip(w, -3e38, 3e38).astype(np.float32)
+    for bits in (4, 8):
+        for mode in (2, 0):
+            codes, scales = run_single(sq, w, bits, mode)
+            assert_same(codes, scales, w, bits, mode, what=f"extreme {shape} bits={bits} mode={mode}")
+
+
 def test_unaligned_views(sq):
     """Channel lengths that leave the output channel base misaligned for wide access."""
     for shape in [(7, 3, 3, 3), (5, 7, 1, 1), (9, 5, 1, 3)]:
