@@ -103,8 +103,7 @@ Plan plan_tensor(const void* w, const void* codes, int64_t N, int64_t K, int lds
                        (reinterpret_cast<uintptr_t>(codes) & 3u) == 0;
   if (K == 9 && (N & 3) == 0 && N <= 4096 && aligned) {
     const int threads = (int)round_up((size_t)N / 4, kWave);
-    const size_t lds = (size_t)144 * threads;  // 9 vectors of 16 bytes per thread
-    if (lds + sizeof(K9Shared) + 64 <= (size_t)lds_limit) return Plan{kK9, threads, lds};
+    return Plan{kK9, threads, round_up((size_t)9 * N, 16)};  // LDS: the channel's int8 codes
   }
   const size_t lds = generic_lds_bytes(N, K);
   if (lds + kStaticLds > (size_t)lds_limit) return Plan{kGeneric, 0, 0};
@@ -309,6 +308,6 @@ const char* squant_status_string(int status) {
   }
 }
 
-int squant_version(void) { return 101; }
+int squant_version(void) { return 102; }
 
 }  // extern "C"

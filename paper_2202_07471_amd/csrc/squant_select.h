@@ -67,12 +67,15 @@ __device__ __forceinline__ void scan_histogram(const uint32_t* hist, uint32_t ne
 }
 
 // Every thread holds NC candidates: value v[q] (0 = none), the byte offset pos[q] of the
-// candidate element inside the channel's int8 codes in LDS, and the kernel index n0 + q.
+// candidate element inside the channel's int8 codes in LDS, and the kernel index
+// n0 + q * nstride (nstride = 1: a thread owns consecutive kernels; nstride = number of
+// kernel-carrying threads: thread t owns kernels t, t + nstride, ...).
 // Flips the selected candidates' codes one step against the channel sum (code -= sgn).
 // Must be called by all threads of the workgroup; sh.list_count must be 0 on entry.
 template <int NC>
 __device__ __forceinline__ void channel_stage(const int32_t (&v)[NC], const int (&pos)[NC], int n0,
-                                              int sgn, uint32_t need, int8_t* code, SelectShared& sh) {
+                                              int nstride, int sgn, uint32_t need, int8_t* code,
+                                              SelectShared& sh) {
   uint32_t key[NC];
   bool live[NC];  // still undecided
 #pragma unroll
@@ -124,7 +127,7 @@ __device__ __forceinline__ void channel_stage(const int32_t (&v)[NC], const int 
       if (live[q]) {
         const uint32_t slot = atomicAdd(&sh.list_count, 1u);
         sh.list_key[slot] = key[q];
-        sh.list_n[slot] = (uint32_t)(n0 + q);
+        sh.list_n[slot] = (uint32_t)(n0 + q * nstride);
       }
     __syncthreads();
 #pragma unroll
@@ -133,35 +136,47 @@ __device__ __forceinline__ void channel_stage(const int32_t (&v)[NC], const int 
         uint32_t rank = 0;
         for (uint32_t e = 0; e < count; ++e) {
           const uint32_t ek = sh.list_key[e], en = sh.list_n[e];
-          rank += (ek > key[q] || (ek == key[q] && en < (uint32_t)(n0 + q))) ? 1u : 0u;
+          rank += (ek > key[q] || (ek == key[q] && en < (uint32_t)(n0 + q * nstride))) ? 1u : 0u;
         }
         if (rank < need) code[pos[q]] = (int8_t)(code[pos[q]] - sgn);
       }
     return;
   }
   // more than kListCap keys equal in all 24 bits: the lowest kernel indices flip.
-  // Threads hold consecutive kernel indices in thread order, so an exclusive prefix
-  // count over threads ranks them.
-  uint32_t mine = 0;
-#pragma unroll
-  for (int q = 0; q < NC; ++q) mine += live[q] ? 1u : 0u;
-  uint32_t incl = mine;
+  // Kernel order is thread order within one q (nstride > 1) or thread order over all q
+  // (nstride = 1), so exclusive prefix counts over the threads rank them.
   const int lane = threadIdx.x & (kWave - 1), wid = threadIdx.x / kWave;
+  const int nw = (blockDim.x + kWave - 1) / kWave;
+  const int rounds = nstride == 1 ? 1 : NC;
+  uint32_t done = 0;  // live keys with a lower kernel index, counted in earlier rounds
+  for (int round = 0; round < rounds; ++round) {
+    uint32_t mine = 0;
 #pragma unroll
-  for (int off = 1; off < kWave; off <<= 1) {
-    const uint32_t o = __shfl_up(incl, off);
-    if (lane >= off) incl += o;
-  }
-  if (lane == kWave - 1) sh.wave_cnt[wid] = incl;
-  __syncthreads();
-  uint32_t base = incl - mine;
-  for (int w = 0; w < wid; ++w) base += sh.wave_cnt[w];
+    for (int q = 0; q < NC; ++q)
+      if (nstride == 1 || q == round) mine += live[q] ? 1u : 0u;
+    uint32_t incl = mine;
 #pragma unroll
-  for (int q = 0; q < NC; ++q)
-    if (live[q]) {
-      if (base < need) code[pos[q]] = (int8_t)(code[pos[q]] - sgn);
-      ++base;
+    for (int off = 1; off < kWave; off <<= 1) {
+      const uint32_t o = __shfl_up(incl, off);
+      if (lane >= off) incl += o;
     }
+    __syncthreads();
+    if (lane == kWave - 1) sh.wave_cnt[wid] = incl;
+    __syncthreads();
+    uint32_t base = done + incl - mine, total = 0;
+    for (int w = 0; w < nw; ++w) {
+      const uint32_t c = sh.wave_cnt[w];
+      if (w < wid) base += c;
+      total += c;
+    }
+#pragma unroll
+    for (int q = 0; q < NC; ++q)
+      if ((nstride == 1 || q == round) && live[q]) {
+        if (base < need) code[pos[q]] = (int8_t)(code[pos[q]] - sgn);
+        ++base;
+      }
+    done += total;
+  }
 }
 
 }  // namespace squant
