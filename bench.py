@@ -54,6 +54,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c5", choices=sorted(WORKLOADS))
     ap.add_argument("--bits", type=int, default=4)
+    ap.add_argument("--mode", default="EKC", choices=["E", "EK", "EKC", "EC"],
+                    help="stages to run; the headline metric is EKC")
     ap.add_argument("--tensors", type=int, default=None, help="truncate the tensor list (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -98,7 +100,7 @@ def main() -> int:
         f"({sum(s.dist == 'student_t3' for s in specs)} Student-t tensors)")
 
     plan = sq.BatchPlan(dws)
-    mode = sq.MODE_EKC
+    mode = sq.MODES[args.mode]
     if args.calibrate_copy:
         a_ = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         b_ = torch.empty_like(a_)
@@ -146,12 +148,12 @@ def main() -> int:
         threads = min(cores, int(env_threads)) if env_threads and env_threads.isdigit() else cores
         sample_params = sum(w.size for w in host_sample)
         t0 = time.perf_counter()
-        ref = [oracle.quantize(w, args.bits, oracle.MODE_EKC, threads=threads) for w in host_sample]
+        ref = [oracle.quantize(w, args.bits, mode, threads=threads) for w in host_sample]
         cpu_s = time.perf_counter() - t0
         t0 = time.perf_counter()
         n1 = max(1, min(4, len(host_sample)))
         for w in host_sample[:n1]:
-            oracle.quantize(w, args.bits, oracle.MODE_EKC, threads=1)
+            oracle.quantize(w, args.bits, mode, threads=1)
         cpu1_s = time.perf_counter() - t0
         p1 = sum(w.size for w in host_sample[:n1])
         # the GPU result of the timed configuration, checked against the same reference
@@ -163,7 +165,7 @@ def main() -> int:
         cpu_baseline = {"value": round(sample_params / cpu_s / 1e9, 5), "unit": "Gparams/s",
                         "cores": threads, "kind": "oracle",
                         "sample": f"first {len(host_sample)} tensors of the workload "
-                                  f"({sample_params} weights), EKC, {threads} threads over output channels",
+                                  f"({sample_params} weights), {args.mode}, {threads} threads over output channels",
                         "single_thread_value": round(p1 / cpu1_s / 1e9, 5),
                         "gpu_mismatches_on_sample": mism}
         log(f"[bench] CPU reference: {sample_params / cpu_s / 1e6:.1f} Mparams/s on {threads} threads, "
@@ -177,7 +179,7 @@ def main() -> int:
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32 in, Q24 int32 perturbations, int8 out",
         "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {desc}", "bits": args.bits, "mode": "EKC",
+        "config": {"workload": f"{args.workload}: {desc}", "bits": args.bits, "mode": args.mode,
                    "tensors": len(specs), "weights": n_params, "output_channels": n_channels,
                    "seed": synth.DEFAULT_SEED},
         "roofline": roofline, "cpu_baseline": cpu_baseline,

@@ -28,27 +28,55 @@ SQ_HD float div_by_reciprocal(float w, float s, float r) {
   return __builtin_fmaf(e1, r, q1);
 }
 
-// compare-exchange: afterwards a >= b
-#define SQ_CE(a, b)                                  \
-  {                                                  \
-    const int32_t hi_ = s[a] > s[b] ? s[a] : s[b];             \
-    const int32_t lo_ = s[a] > s[b] ? s[b] : s[a];             \
-    s[a] = hi_;                                      \
-    s[b] = lo_;                                      \
-  }
-
-// Leaves the five largest of s[0..8] in s[0] >= s[1] >= ... >= s[4].  A 25-exchange
-// sorting network for nine inputs with the three exchanges that only order the four
-// smallest outputs removed; checked exhaustively on all 0/1 inputs by the test-suite.
-SQ_HD void top5_of_9(int32_t (&s)[9]) {
-  SQ_CE(0, 3) SQ_CE(1, 7) SQ_CE(2, 5) SQ_CE(4, 8)
-  SQ_CE(0, 7) SQ_CE(2, 4) SQ_CE(3, 8) SQ_CE(5, 6)
-  SQ_CE(0, 2) SQ_CE(1, 3) SQ_CE(4, 5) SQ_CE(7, 8)
-  SQ_CE(1, 4) SQ_CE(3, 6) SQ_CE(5, 7)
-  SQ_CE(0, 1) SQ_CE(2, 4) SQ_CE(3, 5)
-  SQ_CE(2, 3) SQ_CE(4, 5)
-  SQ_CE(1, 2) SQ_CE(3, 4)
+SQ_HD int32_t imax2(int32_t a, int32_t b) { return a > b ? a : b; }
+SQ_HD int32_t imin2(int32_t a, int32_t b) { return a < b ? a : b; }
+SQ_HD int32_t imax3(int32_t a, int32_t b, int32_t c) { return imax2(imax2(a, b), c); }
+SQ_HD int32_t imin3(int32_t a, int32_t b, int32_t c) { return imin2(imin2(a, b), c); }
+#ifndef SQ_OPT_MED3_ASM
+#define SQ_OPT_MED3_ASM 1
+#endif
+SQ_HD int32_t imed3(int32_t a, int32_t b, int32_t c) {
+#if defined(__HIP_DEVICE_COMPILE__) && SQ_OPT_MED3_ASM
+  int32_t r;
+  asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+#else
+  return imax2(imin2(a, b), imin2(imax2(a, b), c));
+#endif
 }
-#undef SQ_CE
+
+// Leaves the five largest of x[0..8] in t[0] >= t[1] >= ... >= t[4], 25 three-input
+// operations.  View x as a 3x3 matrix: sort the columns (9 ops), then the rows as far as
+// needed (6 ops); rows and columns are then both ordered, so only
+//   a b c
+//   d e .
+//   g . .
+// can hold one of the five largest, a is the largest, e <= min(b, d), c <= b, g <= d.
+// max/min(b, d) give ranks 2 and the runner-up D; c, e, g are sorted (3 ops) and D is
+// inserted into them (5 ops).  Checked on every 0/1 input and on random keys by the
+// test-suite (the operations are monotone, so the 0/1 principle applies).
+SQ_HD void top5_of_9(const int32_t (&x)[9], int32_t (&t)[5]) {
+  int32_t hi[3], mid[3], lo[3];
+#pragma unroll
+  for (int j = 0; j < 3; ++j) {
+    hi[j] = imax3(x[j], x[j + 3], x[j + 6]);
+    mid[j] = imed3(x[j], x[j + 3], x[j + 6]);
+    lo[j] = imin3(x[j], x[j + 3], x[j + 6]);
+  }
+  const int32_t a = imax3(hi[0], hi[1], hi[2]);
+  const int32_t b = imed3(hi[0], hi[1], hi[2]);
+  const int32_t c = imin3(hi[0], hi[1], hi[2]);
+  const int32_t d = imax3(mid[0], mid[1], mid[2]);
+  const int32_t e = imed3(mid[0], mid[1], mid[2]);
+  const int32_t g = imax3(lo[0], lo[1], lo[2]);
+  const int32_t B = imax2(b, d), D = imin2(b, d);
+  const int32_t C = imax3(c, e, g), E = imed3(c, e, g), G = imin3(c, e, g);
+  const int32_t t1 = imin2(D, C), t2 = imin2(t1, E);
+  t[0] = a;
+  t[1] = B;
+  t[2] = imax2(D, C);
+  t[3] = imax2(t1, E);
+  t[4] = imax2(t2, G);
+}
 
 }  // namespace squant

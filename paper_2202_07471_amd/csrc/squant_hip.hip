@@ -308,6 +308,6 @@ const char* squant_status_string(int status) {
   }
 }
 
-int squant_version(void) { return 102; }
+int squant_version(void) { return 103; }
 
 }  // extern "C"

@@ -5,7 +5,7 @@
 // vectors each, so neighbouring lanes read neighbouring kernels and the three loads of a
 // wave cover one contiguous 2304-byte span.  From there SQuant-E, SQuant-K and the
 // Algorithm 3 candidate are pure register arithmetic: the k <= 4 largest same-sign
-// perturbations of a kernel come out of a 22-exchange selection network on unique integer
+// perturbations of a kernel come out of a 25-operation three-input (max3/med3/min3) selection network on unique integer
 // keys (|p| in Q24 above a 4-bit "15 - index" tie-break).  LDS only holds the channel's
 // int8 codes, for the channel-wise flips of SQuant-C (run once per channel on the 4
 // candidates each thread holds) and for a coalesced 16-byte write-out; occupancy is left
@@ -16,6 +16,15 @@
 #include "squant_select.h"
 
 namespace squant {
+
+// tuning switches (compile time)
+#ifndef SQ_OPT_NT_LOAD
+#define SQ_OPT_NT_LOAD 0   // off: the three 12-byte loads of a kernel share cache lines, and
+                           // non-temporal loads were measured 6% slower
+#endif
+#ifndef SQ_OPT_NT_STORE
+#define SQ_OPT_NT_STORE 1  // codes are written once: non-temporal stores (measured 1% faster)
+#endif
 
 typedef float vf3 __attribute__((ext_vector_type(3)));
 typedef float vf4 __attribute__((ext_vector_type(4)));
@@ -31,21 +40,32 @@ __device__ __forceinline__ vf4 load_global_f4(const float* p) {
 }
 __device__ __forceinline__ vf3 load_global_f3(const float* p) {
 #if defined(__HIP_DEVICE_COMPILE__)
+#if SQ_OPT_NT_LOAD
+  return __builtin_nontemporal_load(
+      reinterpret_cast<const __attribute__((address_space(1))) vf3*>(reinterpret_cast<uintptr_t>(p)));
+#else
   return *reinterpret_cast<const __attribute__((address_space(1))) vf3*>(reinterpret_cast<uintptr_t>(p));
+#endif
 #else
   return *reinterpret_cast<const vf3*>(p);
 #endif
 }
 __device__ __forceinline__ void store_global_u4(void* p, vu4 v) {
 #if defined(__HIP_DEVICE_COMPILE__)
+#if SQ_OPT_NT_STORE
+  __builtin_nontemporal_store(
+      v, reinterpret_cast<__attribute__((address_space(1))) vu4*>(reinterpret_cast<uintptr_t>(p)));
+#else
   *reinterpret_cast<__attribute__((address_space(1))) vu4*>(reinterpret_cast<uintptr_t>(p)) = v;
+#endif
 #else
   *reinterpret_cast<vu4*>(p) = v;
 #endif
 }
 __device__ __forceinline__ void store_global_u1(void* p, uint32_t v) {
 #if defined(__HIP_DEVICE_COMPILE__)
-  *reinterpret_cast<__attribute__((address_space(1))) uint32_t*>(reinterpret_cast<uintptr_t>(p)) = v;
+  __builtin_nontemporal_store(
+      v, reinterpret_cast<__attribute__((address_space(1))) uint32_t*>(reinterpret_cast<uintptr_t>(p)));
 #else
   *reinterpret_cast<uint32_t*>(p) = v;
 #endif
@@ -100,14 +120,13 @@ __device__ __forceinline__ void k9_solve(const float (&w)[NW], float s, float rs
   esum += (r ^ smask) - smask;
 
   // unique keys: same-sign elements get (|p| - 1) << 4 | (15 - i) >= 0, all others < 0
-  int32_t key[9], srt[9];
+  int32_t key[9], srt[5];
 #pragma unroll
   for (int i = 0; i < 9; ++i) {
     const uint32_t a = (uint32_t)((P[i] ^ smask) + ~smask);
     key[i] = (int32_t)((a << 4) | (uint32_t)(15 - i));
-    srt[i] = key[i];
   }
-  top5_of_9(srt);
+  top5_of_9(key, srt);
   int32_t s_km1 = 0x7fffffff, s_k = srt[0];      // (k-th, (k+1)-th) largest key, 1-based
   if (k >= 1) { s_km1 = srt[0]; s_k = srt[1]; }
   if (k >= 2) { s_km1 = srt[1]; s_k = srt[2]; }

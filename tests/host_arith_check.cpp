@@ -25,15 +25,17 @@ static long check_network() {
     int32_t s[9], ref[9];
     for (int i = 0; i < 9; ++i) s[i] = ref[i] = (bits >> i) & 1;
     std::sort(ref, ref + 9, std::greater<int32_t>());
-    squant::top5_of_9(s);
-    for (int i = 0; i < 5; ++i) bad += s[i] != ref[i];
+    int32_t top[5];
+    squant::top5_of_9(s, top);
+    for (int i = 0; i < 5; ++i) bad += top[i] != ref[i];
   }
   for (int t = 0; t < 200000; ++t) {
     int32_t s[9], ref[9];
     for (int i = 0; i < 9; ++i) s[i] = ref[i] = (int32_t)(xs() >> (t % 3 == 0 ? 60 : 33)) - (1 << 29);
     std::sort(ref, ref + 9, std::greater<int32_t>());
-    squant::top5_of_9(s);
-    for (int i = 0; i < 5; ++i) bad += s[i] != ref[i];
+    int32_t top[5];
+    squant::top5_of_9(s, top);
+    for (int i = 0; i < 5; ++i) bad += top[i] != ref[i];
   }
   return bad;
 }
