@@ -57,6 +57,10 @@ def main() -> int:
     ap.add_argument("--mode", default="EKC", choices=["E", "EK", "EKC", "EC"],
                     help="stages to run; the headline metric is EKC")
     ap.add_argument("--tensors", type=int, default=None, help="truncate the tensor list (debug)")
+    ap.add_argument("--shape", default=None,
+                    help="cout,cin,kh,kw: replace the workload by --count He-normal tensors of this shape "
+                         "(exploration only; not the headline configuration)")
+    ap.add_argument("--count", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for HBM byte counters)")
@@ -81,13 +85,17 @@ def main() -> int:
 
     config, desc = WORKLOADS[args.workload]
     specs = synth.config_specs(config, n_tensors=args.tensors)
+    if args.shape:
+        shp = tuple(int(v) for v in args.shape.split(","))
+        desc = f"custom: {args.count} x {list(shp)} He-normal"
+        specs = [synth.TensorSpec(9, i, shp, "normal", synth.he_sigma(shp)) for i in range(args.count)]
     n_params = sum(s.numel for s in specs)
     n_channels = sum(s.shape[0] for s in specs)
     log(f"[bench] workload {args.workload}: {len(specs)} tensors, {n_params} weights, "
         f"{n_channels} output channels")
 
     # ---- synthetic weights: generated once on the host, uploaded, a sample kept for the CPU leg
-    cpu_sample_tensors = 64 if config == 5 else len(specs)
+    cpu_sample_tensors = 64 if (config == 5 or args.shape) else len(specs)
     t0 = time.time()
     host_sample, dws = [], []
     for s in specs:
@@ -179,7 +187,7 @@ def main() -> int:
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32 in, Q24 int32 perturbations, int8 out",
         "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {desc}", "bits": args.bits, "mode": args.mode,
+        "config": {"workload": desc if args.shape else f"{args.workload}: {desc}", "bits": args.bits, "mode": args.mode,
                    "tensors": len(specs), "weights": n_params, "output_channels": n_channels,
                    "seed": synth.DEFAULT_SEED},
         "roofline": roofline, "cpu_baseline": cpu_baseline,

@@ -27,6 +27,7 @@ struct LaunchArgs {
   TensorDesc single;        // used when table == nullptr
   const TensorDesc* table;  // device table, n_tensors entries ordered by `first`
   int32_t n_tensors;
+  int32_t total;            // output channels in this launch
   int32_t uniform_m;        // > 0: every tensor of the table has this many channels
   int32_t qmax;
   int32_t mode;
@@ -138,6 +139,28 @@ __device__ __forceinline__ int64_t block_sum_dpp(int32_t v, int64_t* slot) {
   const int64_t w = wave_sum_dpp(v);
   const int wid = threadIdx.x / kWave, nw = (blockDim.x + kWave - 1) / kWave;
   __syncthreads();
+  if ((threadIdx.x & (kWave - 1)) == 0) slot[wid] = w;
+  __syncthreads();
+  int64_t r = slot[0];
+  for (int i = 1; i < nw; ++i) r += slot[i];
+  return r;
+}
+
+// One-barrier versions for callers that pass at least one other workgroup barrier before
+// they reduce into the same slots again (so no wave can still be reading them).
+__device__ __forceinline__ float block_max_dpp1(float v, float* slot) {
+  v = wave_max_dpp(v);
+  const int wid = threadIdx.x / kWave, nw = (blockDim.x + kWave - 1) / kWave;
+  if ((threadIdx.x & (kWave - 1)) == 0) slot[wid] = v;
+  __syncthreads();
+  float r = slot[0];
+  for (int i = 1; i < nw; ++i) r = fmaxf(r, slot[i]);
+  return r;
+}
+
+__device__ __forceinline__ int64_t block_sum_dpp1(int32_t v, int64_t* slot) {
+  const int64_t w = wave_sum_dpp(v);
+  const int wid = threadIdx.x / kWave, nw = (blockDim.x + kWave - 1) / kWave;
   if ((threadIdx.x & (kWave - 1)) == 0) slot[wid] = w;
   __syncthreads();
   int64_t r = slot[0];

@@ -124,10 +124,20 @@ int launch_group(const Group& g, const TensorDesc* d_table, int qmax, int mode, 
     a.table = d_table;
     a.n_tensors = (int)g.t.size();
   }
+  a.total = (int32_t)total;
   a.uniform_m = uniform ? g.t[0].M : 0;
   a.qmax = qmax;
   a.mode = mode;
-  void (*kernel)(LaunchArgs) = g.variant == kK9 ? squant_channel_k9 : squant_channel_generic;
+  typedef void (*kernel_t)(LaunchArgs);
+  static const kernel_t k9_small[4] = {
+      squant_channel_k9<256, SQUANT_MODE_E>, squant_channel_k9<256, SQUANT_MODE_EK>,
+      squant_channel_k9<256, SQUANT_MODE_EKC>, squant_channel_k9<256, SQUANT_MODE_EC>};
+  static const kernel_t k9_large[4] = {
+      squant_channel_k9<1024, SQUANT_MODE_E>, squant_channel_k9<1024, SQUANT_MODE_EK>,
+      squant_channel_k9<1024, SQUANT_MODE_EKC>, squant_channel_k9<1024, SQUANT_MODE_EC>};
+  const kernel_t kernel = g.variant != kK9   ? squant_channel_generic
+                          : g.threads <= 256 ? k9_small[mode]
+                                             : k9_large[mode];
   if (g.lds > 48 * 1024) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds) != hipSuccess) {
@@ -135,7 +145,8 @@ int launch_group(const Group& g, const TensorDesc* d_table, int qmax, int mode, 
       return SQUANT_ERR_DEVICE;
     }
   }
-  hipLaunchKernelGGL(kernel, dim3((unsigned)total), dim3(g.threads), g.lds, st, a);
+  const unsigned grid = (unsigned)total;
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(g.threads), g.lds, st, a);
   if (hipGetLastError() != hipSuccess) return SQUANT_ERR_DEVICE;
   return SQUANT_OK;
 }
@@ -308,6 +319,6 @@ const char* squant_status_string(int status) {
   }
 }
 
-int squant_version(void) { return 103; }
+int squant_version(void) { return 104; }
 
 }  // extern "C"

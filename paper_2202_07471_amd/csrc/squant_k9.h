@@ -78,34 +78,37 @@ struct K9Shared {
 };
 
 // SQuant-E, SQuant-K and the candidate update for one 3x3 kernel held in registers.
-//   w9      the kernel's nine weights are w[W0 .. W0+8]
-//   cf      out: the final codes as floats, plus `keep` (un-flipped) or plus
-//           flip_pos / flip_neg (flipped against a positive / negative sum), so the
-//           caller picks the bias its packing wants
+// Straight-line code on purpose: the four kernels of a thread are scheduled as one region,
+// and a branch between them was measured to cost 20%.
+//   w       the kernel's nine weights are w[W0 .. W0+8]
+//   FAST    take the quotients through the reciprocal rs = 1/s
+//   MODE    SQUANT_MODE_*
+//   cf      out: the final codes as floats
 //   esum    += the kernel's Q24 perturbation sum after SQuant-K
 //   cand_v  Q24 perturbation of the kernel's SQuant-C candidate (0 = none)
 //   cand_i  its element index 0..8
-template <int W0, int NW, bool FAST_DIV>
+//   zero    |= 1 << Q when the kernel's perturbation sum is exactly 0 (its candidate is then
+//           worked out separately, see k9_zero_sum_candidate)
+template <int W0, int NW, bool FAST, int MODE>
 __device__ __forceinline__ void k9_solve(const float (&w)[NW], float s, float rs, float qmaxf,
-                                         int mode, float keep, float flip_pos, float flip_neg,
                                          float (&cf)[9], int32_t& esum, int32_t& cand_v,
-                                         int& cand_i) {
+                                         int& cand_i, uint32_t& zero) {
   float c[9];
   int32_t P[9];
 #pragma unroll
   for (int i = 0; i < 9; ++i) {
-    float x = FAST_DIV ? div_by_reciprocal(w[W0 + i], s, rs)
-                       : w[W0 + i] / s;  // either way the IEEE binary32 quotient
-    x = __builtin_amdgcn_fmed3f(x, -qmaxf, qmaxf);
-    c[i] = rintf(x);
-    const float p = c[i] - x;  // exact
+    // x = w / s: either way the IEEE binary32 quotient
+    const float x = FAST ? div_by_reciprocal(w[W0 + i], s, rs) : w[W0 + i] / s;
+    const float xc = __builtin_amdgcn_fmed3f(x, -qmaxf, qmaxf);
+    c[i] = rintf(xc);
+    const float p = c[i] - xc;  // exact
     P[i] = __float2int_rn(p * 16777216.0f);
   }
   cand_v = 0;
   cand_i = 0;
-  if (mode == SQUANT_MODE_E) {
+  if (MODE == SQUANT_MODE_E) {
 #pragma unroll
-    for (int i = 0; i < 9; ++i) cf[i] = c[i] + keep;
+    for (int i = 0; i < 9; ++i) cf[i] = c[i];
     return;
   }
 
@@ -115,9 +118,10 @@ __device__ __forceinline__ void k9_solve(const float (&w)[NW], float s, float rs
   for (int i = 0; i < 9; ++i) E += P[i];
   const int32_t smask = E >> 31;                 // all ones when the sum is negative
   const int32_t A = (E ^ smask) - smask;         // |E|
-  const int32_t k = (mode == SQUANT_MODE_EC) ? 0 : (int32_t)((uint32_t)(A + kHalf - 1) >> 24);
+  const int32_t k = (MODE == SQUANT_MODE_EC) ? 0 : (int32_t)((uint32_t)(A + kHalf - 1) >> 24);
   const int32_t r = A - (k << 24);               // |sum| left after k flips, < 0: over SQuant
   esum += (r ^ smask) - smask;
+  zero |= (E == 0 ? 1u : 0u) << (W0 / 9);
 
   // unique keys: same-sign elements get (|p| - 1) << 4 | (15 - i) >= 0, all others < 0
   int32_t key[9], srt[5];
@@ -134,102 +138,128 @@ __device__ __forceinline__ void k9_solve(const float (&w)[NW], float s, float rs
   if (k >= 4) { s_km1 = srt[3]; s_k = srt[4]; }
 
   // flip the k largest: code -= sign(E)
-  const float flip = smask ? flip_neg : flip_pos;
+  const float flip = smask ? 1.0f : -1.0f;
 #pragma unroll
-  for (int i = 0; i < 9; ++i) cf[i] = c[i] + (key[i] >= s_km1 ? flip : keep);
+  for (int i = 0; i < 9; ++i) cf[i] = c[i] + (key[i] >= s_km1 ? flip : 0.0f);
+  if (MODE == SQUANT_MODE_EK) return;
 
   // ---- perturbation update (Algorithm 3): the kernel's candidate for SQuant-C ----
   const bool over = r < 0;
   const int32_t ck = over ? s_km1 : s_k;         // over: last flipped; under: first un-flipped
-  if (ck >= 0) {
-    const int32_t mag = (ck >> 4) + 1;           // |p| of that element before any flip
-    const int32_t wv = mag - (over ? kOne : 0);  // over: post-flip value has the opposite sign
-    cand_v = (wv ^ smask) - smask;
-    cand_i = 15 - (ck & 15);
+  const int32_t mag = (ck >> 4) + 1;             // |p| of that element before any flip
+  const int32_t wv = mag - (over ? kOne : 0);    // over: post-flip value has the opposite sign
+  cand_v = ck >= 0 ? (wv ^ smask) - smask : 0;
+  cand_i = ck >= 0 ? 15 - (ck & 15) : 0;
+}
+
+// Cold path: the SQuant-C candidate of a kernel whose perturbation sum is exactly zero
+// (nothing is masked then: the largest |p| of either sign, lowest index first).  Such a
+// kernel has k = 0, so its perturbations are those of plain rounding and are recomputed
+// here from the weights in memory.
+__device__ __noinline__ int2 k9_zero_sum_candidate(const float* wk, float s, float qmaxf) {
+  int32_t best = 0, bv = 0;
+  int bi = 0;
+  for (int i = 0; i < 9; ++i) {
+    float x = wk[i] / s;
+    x = fminf(fmaxf(x, -qmaxf), qmaxf);
+    const float p = rintf(x) - x;
+    const int32_t P = __float2int_rn(p * 16777216.0f);
+    const int32_t ap = P < 0 ? -P : P;
+    if (ap > best) { best = ap; bv = P; bi = i; }
   }
-  if (E == 0) {
-    // nothing is masked when the sum is exactly zero: largest |p| of either sign
-    int32_t best = 0;
-    cand_v = 0;
-    cand_i = 0;
+  return make_int2(bv, bi);  // (candidate perturbation, element index)
+}
+
+// Kernel q of a thread: nine floats at `base` (uniform, the channel's kernels q*G ...)
+// plus the lane's element offset, as three 12-byte loads, into w[9q .. 9q+8].
+__device__ __forceinline__ void k9_load_kernel(float (&w)[36], int q, const float* base,
+                                               uint32_t lane_off) {
 #pragma unroll
-    for (int i = 0; i < 9; ++i) {
-      const int32_t ap = P[i] < 0 ? -P[i] : P[i];
-      if (ap > best) { best = ap; cand_v = P[i]; cand_i = i; }
-    }
+  for (int j = 0; j < 3; ++j) {
+    const vf3 v = load_global_f3(base + (lane_off + 3 * j));
+    w[9 * q + 3 * j] = v.x; w[9 * q + 3 * j + 1] = v.y; w[9 * q + 3 * j + 2] = v.z;
   }
 }
 
-// ---------------------------------------------------------------------------
-// The kernel.  Thread t owns the 3x3 kernels t, t + G, t + 2G, t + 3G (G = cin / 4).
-// ---------------------------------------------------------------------------
-template <bool FAST_DIV>
-__device__ __forceinline__ void k9d_solve_all(const float (&w)[36], float s, float rs, float qmaxf,
-                                              int mode, int8_t* code8, const int (&kn)[4],
-                                              int32_t& esum, int32_t (&cv)[4], int (&cpos)[4]) {
+template <bool FAST, int MODE>
+__device__ __forceinline__ void k9_solve4(const float (&w)[36], float s, float rs, float qmaxf,
+                                          int8_t* code8, int t, int G, int32_t& esum,
+                                          int32_t (&cv)[4], int (&ci)[4], uint32_t& zero) {
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     float cf[9];
-    int ci;
-    if (q == 0) k9_solve<0, 36, FAST_DIV>(w, s, rs, qmaxf, mode, 0.0f, -1.0f, 1.0f, cf, esum, cv[0], ci);
-    if (q == 1) k9_solve<9, 36, FAST_DIV>(w, s, rs, qmaxf, mode, 0.0f, -1.0f, 1.0f, cf, esum, cv[1], ci);
-    if (q == 2) k9_solve<18, 36, FAST_DIV>(w, s, rs, qmaxf, mode, 0.0f, -1.0f, 1.0f, cf, esum, cv[2], ci);
-    if (q == 3) k9_solve<27, 36, FAST_DIV>(w, s, rs, qmaxf, mode, 0.0f, -1.0f, 1.0f, cf, esum, cv[3], ci);
-    cpos[q] = 9 * kn[q] + ci;
+    if (q == 0) k9_solve<0, 36, FAST, MODE>(w, s, rs, qmaxf, cf, esum, cv[0], ci[0], zero);
+    if (q == 1) k9_solve<9, 36, FAST, MODE>(w, s, rs, qmaxf, cf, esum, cv[1], ci[1], zero);
+    if (q == 2) k9_solve<18, 36, FAST, MODE>(w, s, rs, qmaxf, cf, esum, cv[2], ci[2], zero);
+    if (q == 3) k9_solve<27, 36, FAST, MODE>(w, s, rs, qmaxf, cf, esum, cv[3], ci[3], zero);
+    const int n = t + q * G;
 #pragma unroll
-    for (int i = 0; i < 9; ++i) code8[9 * kn[q] + i] = (int8_t)(int)cf[i];
+    for (int i = 0; i < 9; ++i) code8[9 * n + i] = (int8_t)(int)cf[i];
   }
 }
 
-__global__ void __launch_bounds__(1024) squant_channel_k9(LaunchArgs a) {
+// One workgroup per output channel.  Thread t owns the 3x3 kernels t, t + G, t + 2G, t + 3G
+// (G = cin / 4).
+template <int MAX_THREADS, int MODE>
+__global__ void __launch_bounds__(MAX_THREADS) squant_channel_k9(LaunchArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];  // 9*N bytes of codes
   __shared__ K9Shared sh;
+  constexpr bool kChannelStage = MODE == SQUANT_MODE_EKC || MODE == SQUANT_MODE_EC;
+  const int T = blockDim.x, tid = threadIdx.x;
+  const float qmaxf = (float)a.qmax;
+  int8_t* code8 = reinterpret_cast<int8_t*>(smem);
 
   int m;
   const TensorDesc d = locate(a, blockIdx.x, m);
   const int N = d.N, G = N >> 2;
   const int L = 9 * N, nvec = 9 * G;  // nvec = L / 4 dwords of codes
-  const int T = blockDim.x, tid = threadIdx.x;
-  const float qmaxf = (float)a.qmax;
-  int8_t* code8 = reinterpret_cast<int8_t*>(smem);
-  if (tid == 0) sh.sel.list_count = 0;
-
   const bool active = tid < G;
   const int t = active ? tid : 0;  // idle threads shadow thread 0's loads and write nothing
-  const int kn[4] = {t, t + G, t + 2 * G, t + 3 * G};
+  const float* src = d.w + (size_t)m * L;
   float w[36];
-  {
-    const float* src = d.w + (size_t)m * L;
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
-#pragma unroll
-      for (int j = 0; j < 3; ++j) {
-        const vf3 v = load_global_f3(src + 9 * kn[q] + 3 * j);
-        w[9 * q + 3 * j] = v.x; w[9 * q + 3 * j + 1] = v.y; w[9 * q + 3 * j + 2] = v.z;
-      }
+  for (int q = 0; q < 4; ++q) k9_load_kernel(w, q, src + (size_t)q * (9 * G), 9u * (uint32_t)t);
+  if (kChannelStage) {  // state of the channel stage, reset before the first barrier
+    if (tid == 0) sh.sel.list_count = 0;
+    for (int b = tid; b < 256; b += T) sh.sel.hist[b] = 0;
   }
+
   float amax = 0.0f;
 #pragma unroll
   for (int j = 0; j < 36; j += 2) amax = fmaxf(fmaxf(amax, fabsf(w[j])), fabsf(w[j + 1]));
-  amax = block_max_dpp(amax, sh.red_f);
+  amax = block_max_dpp1(amax, sh.red_f);
   const float s = amax > 0.0f ? amax / qmaxf : 1.0f;
   if (tid == 0) d.scales[m] = s;
 
   int32_t esum = 0;
   int32_t cv[4] = {0, 0, 0, 0};
-  int cpos[4] = {0, 0, 0, 0};
+  int ci[4] = {0, 0, 0, 0};
+  uint32_t zero = 0;
   if (active) {
     if (amax >= 0x1p-60f && amax <= 0x1p60f) {  // uniform over the workgroup
-      k9d_solve_all<true>(w, s, 1.0f / s, qmaxf, a.mode, code8, kn, esum, cv, cpos);
+      k9_solve4<true, MODE>(w, s, 1.0f / s, qmaxf, code8, t, G, esum, cv, ci, zero);
     } else {
-      k9d_solve_all<false>(w, s, 0.0f, qmaxf, a.mode, code8, kn, esum, cv, cpos);
+      k9_solve4<false, MODE>(w, s, 0.0f, qmaxf, code8, t, G, esum, cv, ci, zero);
+    }
+    if (kChannelStage && zero != 0) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (zero & (1u << q)) {
+          const int2 z = k9_zero_sum_candidate(src + 9 * (t + q * G), s, qmaxf);
+          cv[q] = z.x;
+          ci[q] = z.y;
+        }
     }
   }
-  if (a.mode == SQUANT_MODE_EKC || a.mode == SQUANT_MODE_EC) {
-    const int64_t ec = block_sum_dpp(esum, sh.red_i);  // its barriers publish the codes
+  if (kChannelStage) {
+    const int64_t ec = block_sum_dpp1(esum, sh.red_i);  // its barrier publishes the codes
     const int sgn = sign_of(ec);
     const int64_t kc = flips_for(ec < 0 ? -ec : ec);
-    if (kc > 0) channel_stage<4>(cv, cpos, tid, G, sgn, (uint32_t)(kc > N ? N : kc), code8, sh.sel);
+    if (kc > 0) {
+      const int cpos[4] = {9 * t + ci[0], 9 * (t + G) + ci[1], 9 * (t + 2 * G) + ci[2],
+                           9 * (t + 3 * G) + ci[3]};
+      channel_stage<4>(cv, cpos, tid, G, sgn, (uint32_t)(kc > N ? N : kc), code8, sh.sel);
+    }
   }
   __syncthreads();
 

@@ -71,7 +71,8 @@ __device__ __forceinline__ void scan_histogram(const uint32_t* hist, uint32_t ne
 // n0 + q * nstride (nstride = 1: a thread owns consecutive kernels; nstride = number of
 // kernel-carrying threads: thread t owns kernels t, t + nstride, ...).
 // Flips the selected candidates' codes one step against the channel sum (code -= sgn).
-// Must be called by all threads of the workgroup; sh.list_count must be 0 on entry.
+// Must be called by all threads of the workgroup; on entry sh.list_count and sh.hist must be
+// zero and a workgroup barrier must lie between their zeroing and this call.
 template <int NC>
 __device__ __forceinline__ void channel_stage(const int32_t (&v)[NC], const int (&pos)[NC], int n0,
                                               int nstride, int sgn, uint32_t need, int8_t* code,
@@ -84,8 +85,10 @@ __device__ __forceinline__ void channel_stage(const int32_t (&v)[NC], const int 
   uint32_t count = 0;
   int shift = 16;
   for (;;) {
-    for (int b = threadIdx.x; b < 256; b += blockDim.x) sh.hist[b] = 0;
-    __syncthreads();
+    if (shift != 16) {  // the first pass finds the histogram already zeroed
+      for (int b = threadIdx.x; b < 256; b += blockDim.x) sh.hist[b] = 0;
+      __syncthreads();
+    }
 #pragma unroll
     for (int q = 0; q < NC; ++q)
       if (live[q]) atomicAdd(&sh.hist[(key[q] >> shift) & 255u], 1u);
