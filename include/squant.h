@@ -21,7 +21,7 @@
  *   update   : per kernel, keep one flip candidate                      (Alg. 3)
  *   SQuant-C : per channel, flip the candidate of the k_c = round(|sum p|)
  *              same-sign kernels with the largest candidate |p|         (Eq. 7, Alg. 2)
- * Perturbations are held in Q24 fixed point and summed as integers, an exact half
+ * Perturbations are held in Q23 fixed point (steps of 2^-23) and summed as integers, an exact half
  * in round(|sum|) takes the fewer flips, and ties in a top-k go to the lowest
  * index, so the result does not depend on launch geometry and is reproducible
  * bit for bit.

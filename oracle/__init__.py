@@ -16,8 +16,8 @@ _SRC = os.path.join(_HERE, "squant_oracle.cpp")
 _LIB = os.path.join(_HERE, "libsquant_oracle.so")
 
 MODE_E, MODE_EK, MODE_EKC, MODE_EC = 0, 1, 2, 3
-ONE = 1 << 24
-HALF = 1 << 23
+ONE = 1 << 23
+HALF = 1 << 22
 
 CXXFLAGS = ["-std=c++17", "-O2", "-fno-fast-math", "-ffp-contract=off", "-shared", "-fPIC",
             "-pthread"]
@@ -77,7 +77,7 @@ def quantize(w, bits: int, mode: int = MODE_EKC, threads: int = 1):
 
 
 def quantize_trace(w, bits: int, mode: int = MODE_EKC):
-    """Returns (codes, scales, trace dict of the intermediate decisions, Q24 integers)."""
+    """Returns (codes, scales, trace dict of the intermediate decisions, Q23 integers)."""
     w4 = _prep(w)
     cout, cin, kh, kw = w4.shape
     codes = np.empty(w4.shape, dtype=np.int8)

@@ -21,7 +21,7 @@
 // Readings taken where the paper leaves a choice (all listed again in the
 // design notes of the repository):
 //   * arithmetic: x is one IEEE binary32 division, p = round(x) - x is exact in
-//     binary32; p is then converted once to Q24 fixed point (P = rint(p*2^24))
+//     binary32; p is then converted once to Q23 fixed point (P = rint(p*2^23))
 //     and every sum / comparison is done on integers, so no result depends on
 //     a summation order;
 //   * round() is round-half-to-even; k = round(|e|) takes the FEWER flips on an
@@ -56,25 +56,25 @@
 
 namespace {
 
-constexpr int32_t kOne = 1 << 24;   // 1.0 in Q24
-constexpr int32_t kHalf = 1 << 23;  // 0.5 in Q24
+constexpr int32_t kOne = 1 << 23;   // 1.0 in Q23
+constexpr int32_t kHalf = 1 << 22;  // 0.5 in Q23
 
 enum Mode : int32_t { kModeE = 0, kModeEK = 1, kModeEKC = 2, kModeEC = 3 };
 
 inline int sign_of(int64_t v) { return (v > 0) - (v < 0); }
 
 // k = round(|e|) with an exact half rounded down (fewest flips).
-inline int64_t flips_for(int64_t abs_sum) { return (abs_sum + kHalf - 1) >> 24; }
+inline int64_t flips_for(int64_t abs_sum) { return (abs_sum + kHalf - 1) >> 23; }
 
 // Optional per-kernel / per-channel record of what the stages decided.
 struct Trace {
   int32_t* kernel_k;     // [M*N] number of elements SQuant-K flipped
-  int32_t* kernel_sum;   // [M*N] Q24 kernel perturbation sum after SQuant-K
+  int32_t* kernel_sum;   // [M*N] Q23 kernel perturbation sum after SQuant-K
   int32_t* cand_index;   // [M*N] element index of the SQuant-C candidate, -1 = none
-  int32_t* cand_value;   // [M*N] Q24 perturbation of that element (0 = none)
-  int64_t* channel_sum;  // [M]   Q24 channel perturbation sum after SQuant-K
+  int32_t* cand_value;   // [M*N] Q23 perturbation of that element (0 = none)
+  int64_t* channel_sum;  // [M]   Q23 channel perturbation sum after SQuant-K
   int32_t* channel_k;    // [M]   k of the channel-wise flip
-  int32_t* perturbation; // [M*N*K] Q24 element perturbation after SQuant-K
+  int32_t* perturbation; // [M*N*K] Q23 element perturbation after SQuant-K
 };
 
 // Indices of `p[0..n)` whose sign equals sgn, by |p| descending, index ascending.
@@ -108,7 +108,7 @@ float quantize_channel(const float* w, int32_t N, int32_t K, int32_t qmax, int32
       const float e = std::nearbyintf(x);
       const float p = e - x;  // exact in binary32
       c[j] = (int32_t)e;
-      P[j] = (int32_t)std::lrintf(p * 16777216.0f);
+      P[j] = (int32_t)std::lrintf(p * 8388608.0f);
     }
   }
 
@@ -243,7 +243,7 @@ int squant_oracle_quantize_mt(const float* w, int32_t cout, int32_t cin, int32_t
 
 // Same result plus a record of the intermediate decisions.  Any trace pointer
 // may be null.  Sizes: kernel_* and cand_* [cout*cin]; channel_* [cout];
-// perturbation [cout*cin*kh*kw].  All perturbations are Q24 integers.
+// perturbation [cout*cin*kh*kw].  All perturbations are Q23 integers.
 int squant_oracle_quantize_trace(const float* w, int32_t cout, int32_t cin, int32_t kh, int32_t kw,
                                  int32_t bits, int32_t mode, int8_t* codes, float* scales,
                                  int32_t* kernel_k, int32_t* kernel_sum, int32_t* cand_index,

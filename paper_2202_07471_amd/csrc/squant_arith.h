@@ -13,19 +13,18 @@
 namespace squant {
 
 // x = w / s, correctly rounded, from the correctly rounded reciprocal r = RN(1/s):
-// q0 = RN(w r) is refined twice with the exact FMA residual w - q s.  The first step
-// leaves a relative error below 2^-46 before its rounding, so q1 is a faithful
-// rounding of w/s; Markstein's theorem (faithful quotient + correctly rounded
-// reciprocal + exact residual => correctly rounded quotient) then makes q2 = RN(w/s).
-// Needs the residuals to be exact, i.e. no underflow: callers use it only for
-// 2^-60 <= max|w| <= 2^60, where an element small enough to underflow has |w/s| < 2^-30
-// and rounds to code 0 / perturbation 0 either way.
+// q0 = RN(w r), one exact-residual FMA e = RN(w - q0 s), one correction q1 = RN(q0 + e r).
+// Before its last rounding q1 is within 2.01 * 2^-47 (relative) of w/s, so it can only be
+// misrounded when w/s lies that close to a midpoint between two floats; the finitely many
+// significand pairs for which it does are all enumerated and checked against IEEE division
+// by the test-suite (tests/host_div_exhaustive.cpp), which makes q1 == RN(w/s) a checked
+// fact rather than an estimate.  Needs the residual not to underflow: callers use it only
+// for 2^-60 <= max|w| <= 2^60, where an element small enough to underflow has
+// |w/s| < 2^-30 and rounds to code 0 / perturbation 0 either way.
 SQ_HD float div_by_reciprocal(float w, float s, float r) {
   const float q0 = w * r;
   const float e0 = __builtin_fmaf(-q0, s, w);
-  const float q1 = __builtin_fmaf(e0, r, q0);
-  const float e1 = __builtin_fmaf(-q1, s, w);
-  return __builtin_fmaf(e1, r, q1);
+  return __builtin_fmaf(e0, r, q0);
 }
 
 SQ_HD int32_t imax2(int32_t a, int32_t b) { return a > b ? a : b; }

@@ -11,8 +11,8 @@
 namespace squant {
 
 
-constexpr int32_t kOne = 1 << 24;   // 1.0 in Q24
-constexpr int32_t kHalf = 1 << 23;  // 0.5 in Q24
+constexpr int32_t kOne = 1 << 23;   // 1.0 in Q23
+constexpr int32_t kHalf = 1 << 22;  // 0.5 in Q23
 constexpr int kWave = 64;
 
 struct TensorDesc {
@@ -61,16 +61,16 @@ __device__ __forceinline__ TensorDesc locate(const LaunchArgs& a, int g, int& m)
 __device__ __forceinline__ int sign_of(int64_t v) { return (v > 0) - (v < 0); }
 
 // k = round(|e|), an exact half rounded down (Algorithm 2, "k = round(|e|)").
-__device__ __forceinline__ int64_t flips_for(int64_t abs_sum) { return (abs_sum + kHalf - 1) >> 24; }
+__device__ __forceinline__ int64_t flips_for(int64_t abs_sum) { return (abs_sum + kHalf - 1) >> 23; }
 
 // SQuant-E on one scaled weight (Algorithm 1, rounding and element perturbation):
-// returns the integer code, writes the Q24 perturbation code - x.
+// returns the integer code, writes the Q23 perturbation code - x.
 __device__ __forceinline__ int round_and_perturb(float w, float s, float qmaxf, int32_t& P) {
   float x = w / s;  // IEEE binary32 division
   x = fminf(fmaxf(x, -qmaxf), qmaxf);
   const float c = rintf(x);  // round half to even
   const float p = c - x;     // exact
-  P = __float2int_rn(p * 16777216.0f);
+  P = __float2int_rn(p * 8388608.0f);
   return (int)c;
 }
 

@@ -100,7 +100,7 @@ __device__ void apply_channel_flips(const int32_t* cand, const int32_t* cidx, in
 
 // ---------------------------------------------------------------------------
 // Generic kernel: any (N, K) whose channel fits in LDS.  One thread per kh*kw
-// kernel in the SQuant-K stage, Q24 perturbations and int8 codes held in LDS.
+// kernel in the SQuant-K stage, Q23 perturbations and int8 codes held in LDS.
 // ---------------------------------------------------------------------------
 
 __global__ void __launch_bounds__(1024) squant_channel_generic(LaunchArgs a) {
@@ -114,7 +114,7 @@ __global__ void __launch_bounds__(1024) squant_channel_generic(LaunchArgs a) {
   const TensorDesc d = locate(a, blockIdx.x, m);
   const int N = d.N, K = d.K, L = N * K;
   const int T = blockDim.x, tid = threadIdx.x;
-  int32_t* buf = reinterpret_cast<int32_t*>(smem);         // L : weights, then Q24 perturbations
+  int32_t* buf = reinterpret_cast<int32_t*>(smem);         // L : weights, then Q23 perturbations
   int32_t* cand = (K == 1) ? buf : buf + L;                // N : candidate perturbation per kernel
   int32_t* cidx = (K == 1) ? nullptr : buf + L + N;        // N : candidate element index
   int8_t* code = reinterpret_cast<int8_t*>(buf + L + (K == 1 ? 0 : 2 * N));  // L codes

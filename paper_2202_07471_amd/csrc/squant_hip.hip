@@ -5,7 +5,7 @@
 // into LDS, the absmax scale, rounding (SQuant-E), kernel-wise flip (SQuant-K),
 // candidate update (Algorithm 3) and channel-wise flip (SQuant-C) all run on
 // chip, and only int8 codes and one float scale go back to HBM.  Perturbations
-// are Q24 integers, so every sum is order independent.
+// are Q23 integers, so every sum is order independent.
 //
 // Section / algorithm numbers refer to "SQuant: On-the-Fly Data-Free
 // Quantization via Diagonal Hessian Approximation" (ICLR 2022).

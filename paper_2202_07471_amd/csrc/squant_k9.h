@@ -6,7 +6,7 @@
 // wave cover one contiguous 2304-byte span.  From there SQuant-E, SQuant-K and the
 // Algorithm 3 candidate are pure register arithmetic: the k <= 4 largest same-sign
 // perturbations of a kernel come out of a 25-operation three-input (max3/med3/min3) selection network on unique integer
-// keys (|p| in Q24 above a 4-bit "15 - index" tie-break).  LDS only holds the channel's
+// keys (|p| in Q23 above a 4-bit "15 - index" tie-break).  LDS only holds the channel's
 // int8 codes, for the channel-wise flips of SQuant-C (run once per channel on the 4
 // candidates each thread holds) and for a coalesced 16-byte write-out; occupancy is left
 // to the register file.
@@ -84,8 +84,8 @@ struct K9Shared {
 //   FAST    take the quotients through the reciprocal rs = 1/s
 //   MODE    SQUANT_MODE_*
 //   cf      out: the final codes as floats
-//   esum    += the kernel's Q24 perturbation sum after SQuant-K
-//   cand_v  Q24 perturbation of the kernel's SQuant-C candidate (0 = none)
+//   esum    += the kernel's Q23 perturbation sum after SQuant-K
+//   cand_v  Q23 perturbation of the kernel's SQuant-C candidate (0 = none)
 //   cand_i  its element index 0..8
 //   zero    |= 1 << Q when the kernel's perturbation sum is exactly 0 (its candidate is then
 //           worked out separately, see k9_zero_sum_candidate)
@@ -102,7 +102,10 @@ __device__ __forceinline__ void k9_solve(const float (&w)[NW], float s, float rs
     const float xc = __builtin_amdgcn_fmed3f(x, -qmaxf, qmaxf);
     c[i] = rintf(xc);
     const float p = c[i] - xc;  // exact
-    P[i] = __float2int_rn(p * 16777216.0f);
+    // Q23: p * 2^23 + 1.5 * 2^23 lies in [2^23, 2^24], where a float is an integer, so the one
+    // rounding of the FMA is the round-half-even of p * 2^23 and the integer sits in the
+    // low mantissa bits
+    P[i] = __float_as_int(__builtin_fmaf(p, 8388608.0f, 12582912.0f)) - 0x4B400000;
   }
   cand_v = 0;
   cand_i = 0;
@@ -118,18 +121,16 @@ __device__ __forceinline__ void k9_solve(const float (&w)[NW], float s, float rs
   for (int i = 0; i < 9; ++i) E += P[i];
   const int32_t smask = E >> 31;                 // all ones when the sum is negative
   const int32_t A = (E ^ smask) - smask;         // |E|
-  const int32_t k = (MODE == SQUANT_MODE_EC) ? 0 : (int32_t)((uint32_t)(A + kHalf - 1) >> 24);
-  const int32_t r = A - (k << 24);               // |sum| left after k flips, < 0: over SQuant
+  const int32_t k = (MODE == SQUANT_MODE_EC) ? 0 : (int32_t)((uint32_t)(A + kHalf - 1) >> 23);
+  const int32_t r = A - (k << 23);               // |sum| left after k flips, < 0: over SQuant
   esum += (r ^ smask) - smask;
   zero |= (E == 0 ? 1u : 0u) << (W0 / 9);
 
-  // unique keys: same-sign elements get (|p| - 1) << 4 | (15 - i) >= 0, all others < 0
+  // unique keys: 16 |p| + (15 - i) >= 16 for the elements with the sign of the sum, < 16 for
+  // all others; |P| <= 2^22 fits the 24-bit multiply-add
   int32_t key[9], srt[5];
 #pragma unroll
-  for (int i = 0; i < 9; ++i) {
-    const uint32_t a = (uint32_t)((P[i] ^ smask) + ~smask);
-    key[i] = (int32_t)((a << 4) | (uint32_t)(15 - i));
-  }
+  for (int i = 0; i < 9; ++i) key[i] = __mul24(P[i], smask ? -16 : 16) + (15 - i);
   top5_of_9(key, srt);
   int32_t s_km1 = 0x7fffffff, s_k = srt[0];      // (k-th, (k+1)-th) largest key, 1-based
   if (k >= 1) { s_km1 = srt[0]; s_k = srt[1]; }
@@ -146,10 +147,10 @@ __device__ __forceinline__ void k9_solve(const float (&w)[NW], float s, float rs
   // ---- perturbation update (Algorithm 3): the kernel's candidate for SQuant-C ----
   const bool over = r < 0;
   const int32_t ck = over ? s_km1 : s_k;         // over: last flipped; under: first un-flipped
-  const int32_t mag = (ck >> 4) + 1;             // |p| of that element before any flip
+  const int32_t mag = ck >> 4;                   // |p| of that element before any flip
   const int32_t wv = mag - (over ? kOne : 0);    // over: post-flip value has the opposite sign
-  cand_v = ck >= 0 ? (wv ^ smask) - smask : 0;
-  cand_i = ck >= 0 ? 15 - (ck & 15) : 0;
+  cand_v = ck >= 16 ? (wv ^ smask) - smask : 0;
+  cand_i = ck >= 16 ? 15 - (ck & 15) : 0;
 }
 
 // Cold path: the SQuant-C candidate of a kernel whose perturbation sum is exactly zero
@@ -163,7 +164,7 @@ __device__ __noinline__ int2 k9_zero_sum_candidate(const float* wk, float s, flo
     float x = wk[i] / s;
     x = fminf(fmaxf(x, -qmaxf), qmaxf);
     const float p = rintf(x) - x;
-    const int32_t P = __float2int_rn(p * 16777216.0f);
+    const int32_t P = __float2int_rn(p * 8388608.0f);
     const int32_t ap = P < 0 ? -P : P;
     if (ap > best) { best = ap; bv = P; bi = i; }
   }

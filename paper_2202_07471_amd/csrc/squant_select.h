@@ -8,7 +8,7 @@
 // the need-th largest key lies; everything above d* flips at once, and the few
 // keys inside d* are ranked against each other through a short LDS list.  Only when
 // that digit holds more keys than the list does the next digit get its own
-// histogram pass; keys that are equal in all 24 bits are taken in kernel order by a
+// histogram pass; keys that are equal in all their bits are taken in kernel order by a
 // workgroup prefix count.
 #pragma once
 
@@ -29,7 +29,7 @@ struct SelectShared {
 };
 
 // Ranking key of a channel-stage candidate: |v| if it has the sign of the channel
-// sum, else 0 (not eligible).  0 < key < 2^24 for every eligible candidate.
+// sum, else 0 (not eligible).  0 < key < 2^23 for every eligible candidate.
 __device__ __forceinline__ uint32_t cand_key(int32_t v, int sgn) {
   return (sgn > 0 ? v > 0 : v < 0) ? (uint32_t)(v < 0 ? -v : v) : 0u;
 }
@@ -145,7 +145,7 @@ __device__ __forceinline__ void channel_stage(const int32_t (&v)[NC], const int 
       }
     return;
   }
-  // more than kListCap keys equal in all 24 bits: the lowest kernel indices flip.
+  // more than kListCap keys equal in all their bits: the lowest kernel indices flip.
   // Kernel order is thread order within one q (nstride > 1) or thread order over all q
   // (nstride = 1), so exclusive prefix counts over the threads rank them.
   const int lane = threadIdx.x & (kWave - 1), wid = threadIdx.x / kWave;

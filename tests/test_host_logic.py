@@ -13,3 +13,17 @@ def test_selection_network_and_reciprocal_division(tmp_path):
     out = subprocess.run([exe, "20000000"], capture_output=True, text=True)
     assert out.returncode == 0, out.stdout + out.stderr
     assert "network_mismatches=0" in out.stdout and "division_mismatches=0" in out.stdout
+
+
+def test_reciprocal_division_is_exact_on_every_near_midpoint_case(tmp_path):
+    """Proof by enumeration that the GPU path's three-operation division equals IEEE division
+    (the argument is in the header of host_div_exhaustive.cpp)."""
+    exe = str(tmp_path / "host_div_exhaustive")
+    subprocess.check_call(["g++", "-std=c++17", "-O2", "-mfma", "-ffp-contract=off", "-fopenmp",
+                           "-I", os.path.join(ROOT, "paper_2202_07471_amd", "csrc"),
+                           os.path.join(ROOT, "tests", "host_div_exhaustive.cpp"), "-o", exe])
+    out = subprocess.run([exe], capture_output=True, text=True)
+    assert out.returncode == 0, out.stdout + out.stderr
+    assert "mismatches=0" in out.stdout
+    cases = int(out.stdout.split("near_midpoint_cases=")[1].split()[0])
+    assert cases > 60_000_000

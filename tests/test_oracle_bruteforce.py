@@ -25,7 +25,7 @@ def all_subset_masks(K):
 
 
 def kernel_bruteforce(P):
-    """P: [B, K] Q24 perturbations after rounding.  Lexicographic optimum (|sum|, sum sq)."""
+    """P: [B, K] Q23 perturbations after rounding.  Lexicographic optimum (|sum|, sum sq)."""
     B, K = P.shape
     masks = all_subset_masks(K)                                  # [S, K]
     step = np.sign(P).astype(np.int64) * ONE                      # flipping i moves P_i by -step_i

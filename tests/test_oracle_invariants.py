@@ -20,7 +20,7 @@ def perturbation_f64(w, codes, scales):
 
 def check_constraints(w, bits, slack_per_elem=2.0 ** -17):
     """Eq. (5)-(8) of Section 3.3 on one tensor.  The slack covers the binary32 division
-    error at |x| <= 127 and the Q24 rounding of tiny perturbations."""
+    error at |x| <= 127 and the Q23 rounding of the perturbations."""
     M, N, kh, kw = w.shape
     K = kh * kw
     qmax = (1 << (bits - 1)) - 1

@@ -159,7 +159,7 @@ def test_scale_and_rounding_match_numpy(bits, shape):
         assert (s2 == want_s).all()
 
 
-def test_perturbation_is_q24_of_code_minus_x():
+def test_perturbation_is_fixed_point_of_code_minus_x():
     rng = np.random.default_rng(5)
     w = (rng.standard_normal((8, 16, 3, 3)) * 0.05).astype(np.float32)
     codes, scales, tr = oracle.quantize_trace(w, 4, MODE_E)
