@@ -220,10 +220,7 @@ __global__ void __launch_bounds__(MAX_THREADS) squant_channel_k9(LaunchArgs a) {
   float w[36];
 #pragma unroll
   for (int q = 0; q < 4; ++q) k9_load_kernel(w, q, src + (size_t)q * (9 * G), 9u * (uint32_t)t);
-  if (kChannelStage) {  // state of the channel stage, reset before the first barrier
-    if (tid == 0) sh.sel.list_count = 0;
-    for (int b = tid; b < 256; b += T) sh.sel.hist[b] = 0;
-  }
+  if (kChannelStage) select_reset(sh.sel);  // before the first barrier
 
   float amax = 0.0f;
 #pragma unroll
@@ -253,7 +250,13 @@ __global__ void __launch_bounds__(MAX_THREADS) squant_channel_k9(LaunchArgs a) {
     }
   }
   if (kChannelStage) {
-    const int64_t ec = block_sum_dpp1(esum, sh.red_i);  // its barrier publishes the codes
+    // candidates into the histogram before the wanted sign is known: one barrier then
+    // publishes the codes, the partial sums and the histogram
+    if (active) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) count_candidate(sh.sel, cv[q]);
+    }
+    const int64_t ec = block_sum_dpp1(esum, sh.red_i);
     const int sgn = sign_of(ec);
     const int64_t kc = flips_for(ec < 0 ? -ec : ec);
     if (kc > 0) {

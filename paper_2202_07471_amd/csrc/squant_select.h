@@ -4,12 +4,15 @@
 //
 // Among the candidates whose sign equals the sign of the channel's accumulated
 // perturbation, the `need` with the largest |v| flip, lowest kernel index first on
-// ties.  One 256-bin LDS histogram of the top key digit finds the digit d* in which
-// the need-th largest key lies; everything above d* flips at once, and the few
-// keys inside d* are ranked against each other through a short LDS list.  Only when
-// that digit holds more keys than the list does the next digit get its own
-// histogram pass; keys that are equal in all their bits are taken in kernel order by a
-// workgroup prefix count.
+// ties.  Every candidate is counted into a 2 x 256-bin LDS histogram of the top 8 bits
+// of |v| (one half per sign) as soon as it exists, i.e. before the channel sum and with
+// it the wanted sign is known, so that ONE workgroup barrier publishes the partial
+// channel sums and the histogram together.  Each wave then scans the half it needs
+// (DPP prefix sums, no second barrier), which gives the digit d* holding the need-th
+// largest key: everything above d* flips at once, and the few keys inside d* are ranked
+// against each other through a short LDS list.  Only when that digit holds more keys
+// than the list do the lower bits get histogram passes of their own; keys that are
+// equal in all their bits are taken in kernel order by a workgroup prefix count.
 #pragma once
 
 #include "squant_common.h"
@@ -17,16 +20,31 @@
 namespace squant {
 
 constexpr int kListCap = 128;
+constexpr int kHistDummy = 512;  // bin of "no candidate"
 constexpr uint32_t kNoDigit = 0xFFFFFFFFu;
 
 struct SelectShared {
-  uint32_t hist[256];
-  uint32_t bcast[4];
+  uint32_t hist[528];  // [0,256): v > 0, [256,512): v < 0, 512: none; 528 = 132 x 16 bytes
   uint32_t list_count;
   uint32_t list_key[kListCap];
   uint32_t list_n[kListCap];
   uint32_t wave_cnt[17];
 };
+
+// Zeroes the histogram and the list counter; a workgroup barrier must follow before
+// count_candidate.
+__device__ __forceinline__ void select_reset(SelectShared& sh) {
+  for (int b = threadIdx.x; b < 132; b += blockDim.x)
+    reinterpret_cast<uint4*>(sh.hist)[b] = make_uint4(0, 0, 0, 0);
+  if (threadIdx.x == 0) sh.list_count = 0;
+}
+
+// Counts one candidate (Q23 perturbation v, 0 = none) into the two-sign histogram.
+__device__ __forceinline__ void count_candidate(SelectShared& sh, int32_t v) {
+  const uint32_t a = (uint32_t)(v < 0 ? -v : v);
+  const uint32_t bin = v == 0 ? (uint32_t)kHistDummy : (((uint32_t)v >> 31) << 8) | (a >> 15);
+  atomicAdd(&sh.hist[bin], 1u);
+}
 
 // Ranking key of a channel-stage candidate: |v| if it has the sign of the channel
 // sum, else 0 (not eligible).  0 < key < 2^23 for every eligible candidate.
@@ -34,36 +52,45 @@ __device__ __forceinline__ uint32_t cand_key(int32_t v, int sgn) {
   return (sgn > 0 ? v > 0 : v < 0) ? (uint32_t)(v < 0 ? -v : v) : 0u;
 }
 
-// Wave 0 scans the 256-bin histogram from the top: finds the largest digit d* such that
-// at least `need` keys have a digit >= d*.  Publishes (d*, need - #keys above d*, hist[d*])
-// in bcast[0..2]; d* = kNoDigit when fewer than `need` keys were counted at all.
-__device__ __forceinline__ void scan_histogram(const uint32_t* hist, uint32_t need, uint32_t* bcast) {
-  if (threadIdx.x < kWave) {
-    const int l = threadIdx.x;
-    const uint32_t h0 = hist[4 * l], h1 = hist[4 * l + 1], h2 = hist[4 * l + 2], h3 = hist[4 * l + 3];
-    const uint32_t mine = h0 + h1 + h2 + h3;
-    uint32_t suf = mine;  // inclusive suffix sum over lanes >= l
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-      const uint32_t o = __shfl_down(suf, off);
-      if (l + off < kWave) suf += o;
-    }
-    const unsigned long long reach = __ballot(suf >= need);
-    if (reach == 0ull) {
-      if (l == 0) { bcast[0] = kNoDigit; bcast[1] = 0; bcast[2] = 0; }
-    } else {
-      const int top = 63 - __builtin_clzll(reach);
-      if (l == top) {
-        uint32_t above = suf - mine;
-        uint32_t digit, cnt;
-        if (above + h3 >= need) { digit = 4 * l + 3; cnt = h3; }
-        else if (above + h3 + h2 >= need) { digit = 4 * l + 2; cnt = h2; above += h3; }
-        else if (above + h3 + h2 + h1 >= need) { digit = 4 * l + 1; cnt = h1; above += h3 + h2; }
-        else { digit = 4 * l; cnt = h0; above += h3 + h2 + h1; }
-        bcast[0] = digit; bcast[1] = need - above; bcast[2] = cnt;
-      }
-    }
-  }
+// Inclusive prefix sum over the 64 lanes of a wave (DPP: row_shr 1, 2, 4, 8 inside each
+// row of 16, then row_bcast 15 into rows 1 and 3, row_bcast 31 into rows 2 and 3).
+__device__ __forceinline__ uint32_t wave_prefix_sum(uint32_t x) {
+  int v = (int)x;
+  v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);
+  v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);
+  return (uint32_t)v;
+}
+
+// Every wave scans 256 histogram bins from the top: finds the largest digit d* such that
+// at least `need` keys have a digit >= d*.  Returns d* (kNoDigit when fewer than `need`
+// keys were counted at all) and sets need_at = need - #keys above d*, count_at = hist[d*].
+// Uniform over the wave; identical in every wave that reads the same histogram.
+__device__ __forceinline__ uint32_t scan_histogram_top(const uint32_t* hist, uint32_t need,
+                                                       uint32_t& need_at, uint32_t& count_at) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int first = 4 * (kWave - 1 - lane);  // lane 0 owns the four highest digits
+  const uint4 h = *reinterpret_cast<const uint4*>(hist + first);  // digits first .. first+3
+  const uint32_t mine = h.x + h.y + h.z + h.w;
+  const uint32_t incl = wave_prefix_sum(mine);  // keys with a digit >= first
+  const unsigned long long reach = __ballot(incl >= need);
+  if (reach == 0ull) { need_at = 0; count_at = 0; return kNoDigit; }
+  const int l = __builtin_ctzll(reach);  // first lane (highest digits) that reaches `need`
+  const uint32_t above0 = (uint32_t)__builtin_amdgcn_readlane((int)(incl - mine), l);
+  const uint32_t h3 = (uint32_t)__builtin_amdgcn_readlane((int)h.w, l);
+  const uint32_t h2 = (uint32_t)__builtin_amdgcn_readlane((int)h.z, l);
+  const uint32_t h1 = (uint32_t)__builtin_amdgcn_readlane((int)h.y, l);
+  const uint32_t h0 = (uint32_t)__builtin_amdgcn_readlane((int)h.x, l);
+  const uint32_t base = 4u * (uint32_t)(kWave - 1 - l);
+  if (above0 + h3 >= need) { need_at = need - above0; count_at = h3; return base + 3; }
+  if (above0 + h3 + h2 >= need) { need_at = need - above0 - h3; count_at = h2; return base + 2; }
+  if (above0 + h3 + h2 + h1 >= need) { need_at = need - above0 - h3 - h2; count_at = h1; return base + 1; }
+  need_at = need - above0 - h3 - h2 - h1;
+  count_at = h0;
+  return base;
 }
 
 // Every thread holds NC candidates: value v[q] (0 = none), the byte offset pos[q] of the
@@ -71,8 +98,8 @@ __device__ __forceinline__ void scan_histogram(const uint32_t* hist, uint32_t ne
 // n0 + q * nstride (nstride = 1: a thread owns consecutive kernels; nstride = number of
 // kernel-carrying threads: thread t owns kernels t, t + nstride, ...).
 // Flips the selected candidates' codes one step against the channel sum (code -= sgn).
-// Must be called by all threads of the workgroup; on entry sh.list_count and sh.hist must be
-// zero and a workgroup barrier must lie between their zeroing and this call.
+// Must be called by all threads of the workgroup, after every candidate has been counted
+// (count_candidate) and a workgroup barrier has passed.
 template <int NC>
 __device__ __forceinline__ void channel_stage(const int32_t (&v)[NC], const int (&pos)[NC], int n0,
                                               int nstride, int sgn, uint32_t need, int8_t* code,
@@ -82,38 +109,44 @@ __device__ __forceinline__ void channel_stage(const int32_t (&v)[NC], const int 
 #pragma unroll
   for (int q = 0; q < NC; ++q) { key[q] = cand_key(v[q], sgn); live[q] = key[q] != 0; }
 
-  uint32_t count = 0;
-  int shift = 16;
-  for (;;) {
-    if (shift != 16) {  // the first pass finds the histogram already zeroed
-      for (int b = threadIdx.x; b < 256; b += blockDim.x) sh.hist[b] = 0;
-      __syncthreads();
-    }
+  // ---- top 8 bits: already in the histogram ----
+  uint32_t count = 0, need_at = 0;
+  const uint32_t digit = scan_histogram_top(sh.hist + (sgn < 0 ? 256 : 0), need, need_at, count);
+  if (digit == kNoDigit) {  // fewer eligible candidates than flips wanted: all of them flip
+#pragma unroll
+    for (int q = 0; q < NC; ++q)
+      if (live[q]) code[pos[q]] = (int8_t)(code[pos[q]] - sgn);
+    return;
+  }
+  need = need_at;
+#pragma unroll
+  for (int q = 0; q < NC; ++q) {
+    if (!live[q]) continue;
+    const uint32_t dq = key[q] >> 15;
+    if (dq > digit) code[pos[q]] = (int8_t)(code[pos[q]] - sgn);
+    if (dq != digit) live[q] = false;
+  }
+
+  // ---- a crowded digit: histogram passes over the lower bits (from bit 7, then bit 0) ----
+  int shift = 15;
+  while (count > (uint32_t)kListCap && shift > 0) {
+    shift = shift == 15 ? 7 : 0;
+    __syncthreads();  // every wave has finished reading the histogram
+    for (int b = threadIdx.x; b < 256; b += blockDim.x) sh.hist[b] = 0;
+    __syncthreads();
 #pragma unroll
     for (int q = 0; q < NC; ++q)
       if (live[q]) atomicAdd(&sh.hist[(key[q] >> shift) & 255u], 1u);
     __syncthreads();
-    scan_histogram(sh.hist, need, sh.bcast);
-    __syncthreads();
-    const uint32_t digit = sh.bcast[0];
-    if (digit == kNoDigit) {  // fewer eligible candidates than flips wanted: all of them flip
-#pragma unroll
-      for (int q = 0; q < NC; ++q)
-        if (live[q]) code[pos[q]] = (int8_t)(code[pos[q]] - sgn);
-      return;
-    }
-    need = sh.bcast[1];
-    count = sh.bcast[2];
+    const uint32_t d2 = scan_histogram_top(sh.hist, need, need_at, count);
+    need = need_at;
 #pragma unroll
     for (int q = 0; q < NC; ++q) {
       if (!live[q]) continue;
       const uint32_t dq = (key[q] >> shift) & 255u;
-      if (dq > digit) code[pos[q]] = (int8_t)(code[pos[q]] - sgn);
-      if (dq != digit) live[q] = false;
+      if (dq > d2) code[pos[q]] = (int8_t)(code[pos[q]] - sgn);
+      if (dq != d2) live[q] = false;
     }
-    if (count <= (uint32_t)kListCap || shift == 0) break;
-    shift -= 8;
-    __syncthreads();  // hist and bcast are reused by the next pass
   }
 
   // `count` candidates are still live (same digits down to `shift`); `need` of them flip
@@ -157,12 +190,7 @@ __device__ __forceinline__ void channel_stage(const int32_t (&v)[NC], const int 
 #pragma unroll
     for (int q = 0; q < NC; ++q)
       if (nstride == 1 || q == round) mine += live[q] ? 1u : 0u;
-    uint32_t incl = mine;
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-      const uint32_t o = __shfl_up(incl, off);
-      if (lane >= off) incl += o;
-    }
+    const uint32_t incl = wave_prefix_sum(mine);
     __syncthreads();
     if (lane == kWave - 1) sh.wave_cnt[wid] = incl;
     __syncthreads();
