@@ -83,15 +83,15 @@ struct K9Shared {
 //   w       the kernel's nine weights are w[W0 .. W0+8]
 //   FAST    take the quotients through the reciprocal rs = 1/s
 //   MODE    SQUANT_MODE_*
-//   cf      out: the final codes as floats
+//   cf      out: the final codes as floats, biased by +128
 //   esum    += the kernel's Q23 perturbation sum after SQuant-K
-//   cand_v  Q23 perturbation of the kernel's SQuant-C candidate (0 = none)
+//   cand_w  the kernel's SQuant-C candidate as a candidate word (squant_select.h)
 //   cand_i  its element index 0..8
 //   zero    |= 1 << Q when the kernel's perturbation sum is exactly 0 (its candidate is then
 //           worked out separately, see k9_zero_sum_candidate)
 template <int W0, int NW, bool FAST, int MODE>
 __device__ __forceinline__ void k9_solve(const float (&w)[NW], float s, float rs, float qmaxf,
-                                         float (&cf)[9], int32_t& esum, int32_t& cand_v,
+                                         float (&cf)[9], int32_t& esum, uint32_t& cand_w,
                                          int& cand_i, uint32_t& zero) {
   float c[9];
   int32_t P[9];
@@ -107,11 +107,11 @@ __device__ __forceinline__ void k9_solve(const float (&w)[NW], float s, float rs
     // low mantissa bits
     P[i] = __float_as_int(__builtin_fmaf(p, 8388608.0f, 12582912.0f)) - 0x4B400000;
   }
-  cand_v = 0;
+  cand_w = kNoCandidate;
   cand_i = 0;
   if (MODE == SQUANT_MODE_E) {
 #pragma unroll
-    for (int i = 0; i < 9; ++i) cf[i] = c[i];
+    for (int i = 0; i < 9; ++i) cf[i] = c[i] + 128.0f;
     return;
   }
 
@@ -139,18 +139,21 @@ __device__ __forceinline__ void k9_solve(const float (&w)[NW], float s, float rs
   if (k >= 4) { s_km1 = srt[3]; s_k = srt[4]; }
 
   // flip the k largest: code -= sign(E)
-  const float flip = smask ? 1.0f : -1.0f;
+  const float flip = smask ? 129.0f : 127.0f;
 #pragma unroll
-  for (int i = 0; i < 9; ++i) cf[i] = c[i] + (key[i] >= s_km1 ? flip : 0.0f);
+  for (int i = 0; i < 9; ++i) cf[i] = c[i] + (key[i] >= s_km1 ? flip : 128.0f);
   if (MODE == SQUANT_MODE_EK) return;
 
   // ---- perturbation update (Algorithm 3): the kernel's candidate for SQuant-C ----
   const bool over = r < 0;
   const int32_t ck = over ? s_km1 : s_k;         // over: last flipped; under: first un-flipped
-  const int32_t mag = ck >> 4;                   // |p| of that element before any flip
-  const int32_t wv = mag - (over ? kOne : 0);    // over: post-flip value has the opposite sign
-  cand_v = ck >= 16 ? (wv ^ smask) - smask : 0;
-  cand_i = ck >= 16 ? 15 - (ck & 15) : 0;
+  const uint32_t mag = (uint32_t)ck >> 4;        // |p| of that element before any flip
+  // over: the post-flip value kOne - mag with the sign opposite to the sum; under: mag with
+  // the sign of the sum
+  const uint32_t absv = over ? (uint32_t)kOne - mag : mag;
+  const uint32_t neg = (over ? ~(uint32_t)smask : (uint32_t)smask) & (1u << 23);
+  cand_w = ck >= 16 ? (absv | neg) : kNoCandidate;
+  cand_i = 15 - (ck & 15);
 }
 
 // Cold path: the SQuant-C candidate of a kernel whose perturbation sum is exactly zero
@@ -184,8 +187,8 @@ __device__ __forceinline__ void k9_load_kernel(float (&w)[36], int q, const floa
 
 template <bool FAST, int MODE>
 __device__ __forceinline__ void k9_solve4(const float (&w)[36], float s, float rs, float qmaxf,
-                                          int8_t* code8, int t, int G, int32_t& esum,
-                                          int32_t (&cv)[4], int (&ci)[4], uint32_t& zero) {
+                                          uint8_t* code8, int t, int G, int32_t& esum,
+                                          uint32_t (&cv)[4], int (&ci)[4], uint32_t& zero) {
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     float cf[9];
@@ -195,7 +198,7 @@ __device__ __forceinline__ void k9_solve4(const float (&w)[36], float s, float r
     if (q == 3) k9_solve<27, 36, FAST, MODE>(w, s, rs, qmaxf, cf, esum, cv[3], ci[3], zero);
     const int n = t + q * G;
 #pragma unroll
-    for (int i = 0; i < 9; ++i) code8[9 * n + i] = (int8_t)(int)cf[i];
+    for (int i = 0; i < 9; ++i) code8[9 * n + i] = (uint8_t)(int)cf[i];
   }
 }
 
@@ -208,7 +211,7 @@ __global__ void __launch_bounds__(MAX_THREADS) squant_channel_k9(LaunchArgs a) {
   constexpr bool kChannelStage = MODE == SQUANT_MODE_EKC || MODE == SQUANT_MODE_EC;
   const int T = blockDim.x, tid = threadIdx.x;
   const float qmaxf = (float)a.qmax;
-  int8_t* code8 = reinterpret_cast<int8_t*>(smem);
+  uint8_t* code8 = reinterpret_cast<uint8_t*>(smem);  // biased codes: code + 128
 
   int m;
   const TensorDesc d = locate(a, blockIdx.x, m);
@@ -230,7 +233,7 @@ __global__ void __launch_bounds__(MAX_THREADS) squant_channel_k9(LaunchArgs a) {
   if (tid == 0) d.scales[m] = s;
 
   int32_t esum = 0;
-  int32_t cv[4] = {0, 0, 0, 0};
+  uint32_t cv[4] = {kNoCandidate, kNoCandidate, kNoCandidate, kNoCandidate};
   int ci[4] = {0, 0, 0, 0};
   uint32_t zero = 0;
   if (active) {
@@ -244,7 +247,7 @@ __global__ void __launch_bounds__(MAX_THREADS) squant_channel_k9(LaunchArgs a) {
       for (int q = 0; q < 4; ++q)
         if (zero & (1u << q)) {
           const int2 z = k9_zero_sum_candidate(src + 9 * (t + q * G), s, qmaxf);
-          cv[q] = z.x;
+          cv[q] = candidate_word(z.x);
           ci[q] = z.y;
         }
     }
@@ -262,7 +265,8 @@ __global__ void __launch_bounds__(MAX_THREADS) squant_channel_k9(LaunchArgs a) {
     if (kc > 0) {
       const int cpos[4] = {9 * t + ci[0], 9 * (t + G) + ci[1], 9 * (t + 2 * G) + ci[2],
                            9 * (t + 3 * G) + ci[3]};
-      channel_stage<4>(cv, cpos, tid, G, sgn, (uint32_t)(kc > N ? N : kc), code8, sh.sel);
+      channel_stage<4>(cv, cpos, tid, G, sgn, (uint32_t)(kc > N ? N : kc),
+                       reinterpret_cast<uint32_t*>(smem), sh.sel);
     }
   }
   __syncthreads();
@@ -270,10 +274,10 @@ __global__ void __launch_bounds__(MAX_THREADS) squant_channel_k9(LaunchArgs a) {
   int8_t* out = d.codes + (size_t)m * L;
   if ((nvec & 3) == 0 && (reinterpret_cast<uintptr_t>(out) & 15u) == 0) {
     const vu4* src4 = reinterpret_cast<const vu4*>(smem);
-    for (int j = tid; j < (nvec >> 2); j += T) store_global_u4(out + 16 * j, src4[j]);
+    for (int j = tid; j < (nvec >> 2); j += T) store_global_u4(out + 16 * j, src4[j] ^ 0x80808080u);
   } else {
     const uint32_t* code32 = reinterpret_cast<const uint32_t*>(smem);
-    for (int j = tid; j < nvec; j += T) store_global_u1(out + 4 * j, code32[j]);
+    for (int j = tid; j < nvec; j += T) store_global_u1(out + 4 * j, code32[j] ^ 0x80808080u);
   }
 }
 

@@ -39,17 +39,32 @@ __device__ __forceinline__ void select_reset(SelectShared& sh) {
   if (threadIdx.x == 0) sh.list_count = 0;
 }
 
-// Counts one candidate (Q23 perturbation v, 0 = none) into the two-sign histogram.
-__device__ __forceinline__ void count_candidate(SelectShared& sh, int32_t v) {
+// A candidate travels as one word: |v| (Q23, 0 < |v| < 2^23) in bits 0..22, bit 23 set when
+// v < 0, and kNoCandidate (bit 24) when the kernel has none.  word >> 15 is then directly
+// the histogram bin: 256 * (v < 0) + top 8 bits of |v|, or 512.
+constexpr uint32_t kNoCandidate = 1u << 24;
+__device__ __forceinline__ uint32_t candidate_word(int32_t v) {
   const uint32_t a = (uint32_t)(v < 0 ? -v : v);
-  const uint32_t bin = v == 0 ? (uint32_t)kHistDummy : (((uint32_t)v >> 31) << 8) | (a >> 15);
-  atomicAdd(&sh.hist[bin], 1u);
+  return v == 0 ? kNoCandidate : (a | (v < 0 ? 1u << 23 : 0u));
+}
+
+// Counts one candidate into the two-sign histogram.
+__device__ __forceinline__ void count_candidate(SelectShared& sh, uint32_t word) {
+  atomicAdd(&sh.hist[word >> 15], 1u);
 }
 
 // Ranking key of a channel-stage candidate: |v| if it has the sign of the channel
 // sum, else 0 (not eligible).  0 < key < 2^23 for every eligible candidate.
 __device__ __forceinline__ uint32_t cand_key(int32_t v, int sgn) {
   return (sgn > 0 ? v > 0 : v < 0) ? (uint32_t)(v < 0 ? -v : v) : 0u;
+}
+
+// One step against the channel sum for the code at byte `pos` of the channel's codes in
+// LDS.  The codes are held biased (code + 128, 1..255), so the +-1 can be added to the
+// whole dword without a carry or borrow ever leaving the byte.
+__device__ __forceinline__ void flip_code(uint32_t* code32, int pos, int sgn) {
+  const uint32_t delta = sgn > 0 ? 0xFFFFFFFFu : 1u;
+  atomicAdd(&code32[pos >> 2], delta << ((pos & 3) * 8));
 }
 
 // Inclusive prefix sum over the 64 lanes of a wave (DPP: row_shr 1, 2, 4, 8 inside each
@@ -93,38 +108,42 @@ __device__ __forceinline__ uint32_t scan_histogram_top(const uint32_t* hist, uin
   return base;
 }
 
-// Every thread holds NC candidates: value v[q] (0 = none), the byte offset pos[q] of the
-// candidate element inside the channel's int8 codes in LDS, and the kernel index
+// Every thread holds NC candidates: the candidate word cw[q], the byte offset pos[q] of the
+// candidate element inside the channel's biased codes in LDS, and the kernel index
 // n0 + q * nstride (nstride = 1: a thread owns consecutive kernels; nstride = number of
 // kernel-carrying threads: thread t owns kernels t, t + nstride, ...).
 // Flips the selected candidates' codes one step against the channel sum (code -= sgn).
 // Must be called by all threads of the workgroup, after every candidate has been counted
 // (count_candidate) and a workgroup barrier has passed.
 template <int NC>
-__device__ __forceinline__ void channel_stage(const int32_t (&v)[NC], const int (&pos)[NC], int n0,
-                                              int nstride, int sgn, uint32_t need, int8_t* code,
+__device__ __forceinline__ void channel_stage(const uint32_t (&cw)[NC], const int (&pos)[NC], int n0,
+                                              int nstride, int sgn, uint32_t need, uint32_t* code32,
                                               SelectShared& sh) {
+  const uint32_t half = sgn < 0 ? 256u : 0u;
   uint32_t key[NC];
-  bool live[NC];  // still undecided
+  bool live[NC];  // eligible and still undecided
+  uint32_t dq[NC];
 #pragma unroll
-  for (int q = 0; q < NC; ++q) { key[q] = cand_key(v[q], sgn); live[q] = key[q] != 0; }
+  for (int q = 0; q < NC; ++q) {
+    dq[q] = (cw[q] >> 15) - half;  // top digit, < 256 exactly for the candidates of the wanted sign
+    live[q] = dq[q] < 256u;
+    key[q] = cw[q] & 0x7FFFFFu;
+  }
 
   // ---- top 8 bits: already in the histogram ----
   uint32_t count = 0, need_at = 0;
-  const uint32_t digit = scan_histogram_top(sh.hist + (sgn < 0 ? 256 : 0), need, need_at, count);
+  const uint32_t digit = scan_histogram_top(sh.hist + half, need, need_at, count);
   if (digit == kNoDigit) {  // fewer eligible candidates than flips wanted: all of them flip
 #pragma unroll
     for (int q = 0; q < NC; ++q)
-      if (live[q]) code[pos[q]] = (int8_t)(code[pos[q]] - sgn);
+      if (live[q]) flip_code(code32, pos[q], sgn);
     return;
   }
   need = need_at;
 #pragma unroll
   for (int q = 0; q < NC; ++q) {
-    if (!live[q]) continue;
-    const uint32_t dq = key[q] >> 15;
-    if (dq > digit) code[pos[q]] = (int8_t)(code[pos[q]] - sgn);
-    if (dq != digit) live[q] = false;
+    if (live[q] && dq[q] > digit) flip_code(code32, pos[q], sgn);
+    live[q] = dq[q] == digit;
   }
 
   // ---- a crowded digit: histogram passes over the lower bits (from bit 7, then bit 0) ----
@@ -144,7 +163,7 @@ __device__ __forceinline__ void channel_stage(const int32_t (&v)[NC], const int 
     for (int q = 0; q < NC; ++q) {
       if (!live[q]) continue;
       const uint32_t dq = (key[q] >> shift) & 255u;
-      if (dq > d2) code[pos[q]] = (int8_t)(code[pos[q]] - sgn);
+      if (dq > d2) flip_code(code32, pos[q], sgn);
       if (dq != d2) live[q] = false;
     }
   }
@@ -153,7 +172,7 @@ __device__ __forceinline__ void channel_stage(const int32_t (&v)[NC], const int 
   if (count == need) {
 #pragma unroll
     for (int q = 0; q < NC; ++q)
-      if (live[q]) code[pos[q]] = (int8_t)(code[pos[q]] - sgn);
+      if (live[q]) flip_code(code32, pos[q], sgn);
     return;
   }
   if (count <= (uint32_t)kListCap) {
@@ -174,7 +193,7 @@ __device__ __forceinline__ void channel_stage(const int32_t (&v)[NC], const int 
           const uint32_t ek = sh.list_key[e], en = sh.list_n[e];
           rank += (ek > key[q] || (ek == key[q] && en < (uint32_t)(n0 + q * nstride))) ? 1u : 0u;
         }
-        if (rank < need) code[pos[q]] = (int8_t)(code[pos[q]] - sgn);
+        if (rank < need) flip_code(code32, pos[q], sgn);
       }
     return;
   }
@@ -203,7 +222,7 @@ __device__ __forceinline__ void channel_stage(const int32_t (&v)[NC], const int 
 #pragma unroll
     for (int q = 0; q < NC; ++q)
       if ((nstride == 1 || q == round) && live[q]) {
-        if (base < need) code[pos[q]] = (int8_t)(code[pos[q]] - sgn);
+        if (base < need) flip_code(code32, pos[q], sgn);
         ++base;
       }
     done += total;
