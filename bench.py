@@ -50,8 +50,9 @@ def load_traffic(kernel_version: int):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50,
+                    help="untimed steps first; the GPU needs a few tens of launches to settle its clocks")
     ap.add_argument("--workload", default="c5", choices=sorted(WORKLOADS))
     ap.add_argument("--bits", type=int, default=4)
     ap.add_argument("--mode", default="EKC", choices=["E", "EK", "EKC", "EC"],
@@ -144,6 +145,8 @@ def main() -> int:
                 "kernel": "squant solver kernel(s) of the batched call",
                 "kernel_ms_avg": round(k_avg_ms, 4), "kernel_ms_min": round(float(np.min(kernel_ms)), 4),
                 "algorithmic_bytes_per_launch": algo_bytes}
+    if os.environ.get("SQUANT_BENCH_TRACE"):
+        log("[bench] kernel ms per step: " + " ".join(f"{v:.3f}" for v in kernel_ms))
     log(f"[bench] {ms_per_step:.4f} ms/step wall, kernel avg {k_avg_ms:.4f} ms -> "
         f"{value:.1f} Gparams/s, {achieved:.0f} GB/s algorithmic ({100 * achieved / HBM_PEAK_GBS:.1f}% of peak)")
 
@@ -185,7 +188,7 @@ def main() -> int:
         "metric": "Gparams/s quantized (4-bit, SQuant-EKC) + achieved HBM GB/s vs peak",
         "value": round(value, 2), "unit": "Gparams/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f32 in, Q24 int32 perturbations, int8 out",
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32+int32",
         "data": "synthetic",
         "config": {"workload": desc if args.shape else f"{args.workload}: {desc}", "bits": args.bits, "mode": args.mode,
                    "tensors": len(specs), "weights": n_params, "output_channels": n_channels,

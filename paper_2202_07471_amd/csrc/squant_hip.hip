@@ -27,7 +27,7 @@ namespace {
 using namespace squant;
 
 // Copies a chunk of descriptors passed by value into the device table.
-constexpr int kDescChunk = 64;
+constexpr int kDescChunk = 256;  // 10 KB of by-value kernel arguments per writer launch
 struct DescChunk { TensorDesc t[kDescChunk]; };
 __global__ void write_table(DescChunk c, int count, TensorDesc* table) {
   const int i = threadIdx.x;
@@ -319,6 +319,6 @@ const char* squant_status_string(int status) {
   }
 }
 
-int squant_version(void) { return 104; }
+int squant_version(void) { return 110; }
 
 }  // extern "C"
