@@ -21,6 +21,7 @@
 #include "squant_common.h"
 #include "squant_generic.h"
 #include "squant_k9.h"
+#include "squant_k1.h"
 
 namespace {
 
@@ -84,7 +85,11 @@ struct KernelTimer {
 thread_local KernelTimer g_timer;
 void timer_mark(bool start, hipStream_t st);
 
-enum Variant { kGeneric = 0, kK9 = 1 };
+enum Variant {
+  kGeneric = 0,
+  kK9x1 = 1, kK9x2 = 2, kK9x4 = 3,             // 3x3 kernels per thread: 1, 2, 4
+  kK1x1 = 4, kK1x2 = 5, kK1x4 = 6, kK1x8 = 7  // 1x1 / FC: 16-byte vectors per thread: 1, 2, 4, 8
+};
 
 struct Group {
   int variant;
@@ -102,8 +107,24 @@ Plan plan_tensor(const void* w, const void* codes, int64_t N, int64_t K, int lds
   const bool aligned = (reinterpret_cast<uintptr_t>(w) & 15u) == 0 &&
                        (reinterpret_cast<uintptr_t>(codes) & 3u) == 0;
   if (K == 9 && (N & 3) == 0 && N <= 4096 && aligned) {
-    const int threads = (int)round_up((size_t)N / 4, kWave);
-    return Plan{kK9, threads, round_up((size_t)9 * N, 16)};  // LDS: the channel's int8 codes
+    // kernels per thread: the largest of 4, 2, 1 that keeps the waves fullest
+    int kpt = 4;
+    double best = 0.0;
+    for (int c : {4, 2, 1}) {
+      const size_t th = round_up((size_t)N / c, kWave);
+      if (th > 256 && c != 4) continue;
+      const double fill = (double)(N / c) / (double)th;
+      if (fill > best + 1e-9) { best = fill; kpt = c; }
+    }
+    const int threads = (int)round_up((size_t)N / kpt, kWave);
+    const int variant = kpt == 4 ? kK9x4 : kpt == 2 ? kK9x2 : kK9x1;
+    return Plan{variant, threads, round_up((size_t)9 * N, 16)};  // LDS: the channel's int8 codes
+  }
+  if (K == 1 && (N & 3) == 0 && N <= 32768 && aligned) {
+    const int nv = N <= 1024 ? 1 : N <= 2048 ? 2 : N <= 4096 ? 4 : 8;
+    const int threads = (int)round_up(((size_t)N / 4 + nv - 1) / nv, kWave);
+    const int variant = nv == 1 ? kK1x1 : nv == 2 ? kK1x2 : nv == 4 ? kK1x4 : kK1x8;
+    return Plan{variant, threads, round_up((size_t)N, 16)};  // LDS: the channel's int8 codes
   }
   const size_t lds = generic_lds_bytes(N, K);
   if (lds + kStaticLds > (size_t)lds_limit) return Plan{kGeneric, 0, 0};
@@ -129,15 +150,31 @@ int launch_group(const Group& g, const TensorDesc* d_table, int qmax, int mode, 
   a.qmax = qmax;
   a.mode = mode;
   typedef void (*kernel_t)(LaunchArgs);
-  static const kernel_t k9_small[4] = {
-      squant_channel_k9<256, SQUANT_MODE_E>, squant_channel_k9<256, SQUANT_MODE_EK>,
-      squant_channel_k9<256, SQUANT_MODE_EKC>, squant_channel_k9<256, SQUANT_MODE_EC>};
-  static const kernel_t k9_large[4] = {
-      squant_channel_k9<1024, SQUANT_MODE_E>, squant_channel_k9<1024, SQUANT_MODE_EK>,
-      squant_channel_k9<1024, SQUANT_MODE_EKC>, squant_channel_k9<1024, SQUANT_MODE_EC>};
-  const kernel_t kernel = g.variant != kK9   ? squant_channel_generic
-                          : g.threads <= 256 ? k9_small[mode]
-                                             : k9_large[mode];
+#define SQ_K9_ROW(T, KPT)                                                                     \
+  {squant_channel_k9<T, SQUANT_MODE_E, KPT>, squant_channel_k9<T, SQUANT_MODE_EK, KPT>,       \
+   squant_channel_k9<T, SQUANT_MODE_EKC, KPT>, squant_channel_k9<T, SQUANT_MODE_EC, KPT>}
+  static const kernel_t k9x1[4] = SQ_K9_ROW(256, 1);
+  static const kernel_t k9x2[4] = SQ_K9_ROW(256, 2);
+  static const kernel_t k9x4[4] = SQ_K9_ROW(256, 4);
+  static const kernel_t k9x4_large[4] = SQ_K9_ROW(1024, 4);
+#undef SQ_K9_ROW
+#define SQ_K1_ROW(T, NV)                                                                      \
+  {squant_channel_k1<T, SQUANT_MODE_E, NV>, squant_channel_k1<T, SQUANT_MODE_E, NV>,          \
+   squant_channel_k1<T, SQUANT_MODE_EKC, NV>, squant_channel_k1<T, SQUANT_MODE_EKC, NV>}
+  // (for one-element kernels E&K equals E and E&C equals E&K&C)
+  static const kernel_t k1x1[4] = SQ_K1_ROW(256, 1);
+  static const kernel_t k1x2[4] = SQ_K1_ROW(256, 2);
+  static const kernel_t k1x4[4] = SQ_K1_ROW(256, 4);
+  static const kernel_t k1x8[4] = SQ_K1_ROW(1024, 8);
+#undef SQ_K1_ROW
+  const kernel_t kernel = g.variant == kK1x1   ? k1x1[mode]
+                          : g.variant == kK1x2 ? k1x2[mode]
+                          : g.variant == kK1x4 ? k1x4[mode]
+                          : g.variant == kK1x8 ? k1x8[mode]
+                          : g.variant == kK9x1 ? k9x1[mode]
+                          : g.variant == kK9x2 ? k9x2[mode]
+                          : g.variant == kK9x4 ? (g.threads <= 256 ? k9x4[mode] : k9x4_large[mode])
+                                               : squant_channel_generic;
   if (g.lds > 48 * 1024) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds) != hipSuccess) {
@@ -319,6 +356,6 @@ const char* squant_status_string(int status) {
   }
 }
 
-int squant_version(void) { return 110; }
+int squant_version(void) { return 112; }
 
 }  // extern "C"

@@ -80,7 +80,7 @@ struct K9Shared {
 // SQuant-E, SQuant-K and the candidate update for one 3x3 kernel held in registers.
 // Straight-line code on purpose: the four kernels of a thread are scheduled as one region,
 // and a branch between them was measured to cost 20%.
-//   w       the kernel's nine weights are w[W0 .. W0+8]
+//   w, q    the kernel's nine weights are w[9q .. 9q+8]
 //   FAST    take the quotients through the reciprocal rs = 1/s
 //   MODE    SQUANT_MODE_*
 //   cf      out: the final codes as floats, biased by +128
@@ -89,10 +89,11 @@ struct K9Shared {
 //   cand_i  its element index 0..8
 //   zero    |= 1 << Q when the kernel's perturbation sum is exactly 0 (its candidate is then
 //           worked out separately, see k9_zero_sum_candidate)
-template <int W0, int NW, bool FAST, int MODE>
-__device__ __forceinline__ void k9_solve(const float (&w)[NW], float s, float rs, float qmaxf,
+template <int NW, bool FAST, int MODE>
+__device__ __forceinline__ void k9_solve(const float (&w)[NW], int q, float s, float rs, float qmaxf,
                                          float (&cf)[9], int32_t& esum, uint32_t& cand_w,
                                          int& cand_i, uint32_t& zero) {
+  const int W0 = 9 * q;  // a constant once the caller's loop over q is unrolled
   float c[9];
   int32_t P[9];
 #pragma unroll
@@ -124,7 +125,7 @@ __device__ __forceinline__ void k9_solve(const float (&w)[NW], float s, float rs
   const int32_t k = (MODE == SQUANT_MODE_EC) ? 0 : (int32_t)((uint32_t)(A + kHalf - 1) >> 23);
   const int32_t r = A - (k << 23);               // |sum| left after k flips, < 0: over SQuant
   esum += (r ^ smask) - smask;
-  zero |= (E == 0 ? 1u : 0u) << (W0 / 9);
+  zero |= (E == 0 ? 1u : 0u) << q;
 
   // unique keys: 16 |p| + (15 - i) >= 16 for the elements with the sign of the sum, < 16 for
   // all others; |P| <= 2^22 fits the 24-bit multiply-add
@@ -176,7 +177,8 @@ __device__ __noinline__ int2 k9_zero_sum_candidate(const float* wk, float s, flo
 
 // Kernel q of a thread: nine floats at `base` (uniform, the channel's kernels q*G ...)
 // plus the lane's element offset, as three 12-byte loads, into w[9q .. 9q+8].
-__device__ __forceinline__ void k9_load_kernel(float (&w)[36], int q, const float* base,
+template <int NW>
+__device__ __forceinline__ void k9_load_kernel(float (&w)[NW], int q, const float* base,
                                                uint32_t lane_off) {
 #pragma unroll
   for (int j = 0; j < 3; ++j) {
@@ -185,26 +187,24 @@ __device__ __forceinline__ void k9_load_kernel(float (&w)[36], int q, const floa
   }
 }
 
-template <bool FAST, int MODE>
-__device__ __forceinline__ void k9_solve4(const float (&w)[36], float s, float rs, float qmaxf,
-                                          uint8_t* code8, int t, int G, int32_t& esum,
-                                          uint32_t (&cv)[4], int (&ci)[4], uint32_t& zero) {
+template <int KPT, bool FAST, int MODE>
+__device__ __forceinline__ void k9_solve_all(const float (&w)[9 * KPT], float s, float rs, float qmaxf,
+                                             uint8_t* code8, int t, int G, int32_t& esum,
+                                             uint32_t (&cv)[KPT], int (&ci)[KPT], uint32_t& zero) {
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
+  for (int q = 0; q < KPT; ++q) {
     float cf[9];
-    if (q == 0) k9_solve<0, 36, FAST, MODE>(w, s, rs, qmaxf, cf, esum, cv[0], ci[0], zero);
-    if (q == 1) k9_solve<9, 36, FAST, MODE>(w, s, rs, qmaxf, cf, esum, cv[1], ci[1], zero);
-    if (q == 2) k9_solve<18, 36, FAST, MODE>(w, s, rs, qmaxf, cf, esum, cv[2], ci[2], zero);
-    if (q == 3) k9_solve<27, 36, FAST, MODE>(w, s, rs, qmaxf, cf, esum, cv[3], ci[3], zero);
+    k9_solve<9 * KPT, FAST, MODE>(w, q, s, rs, qmaxf, cf, esum, cv[q], ci[q], zero);
     const int n = t + q * G;
 #pragma unroll
     for (int i = 0; i < 9; ++i) code8[9 * n + i] = (uint8_t)(int)cf[i];
   }
 }
 
-// One workgroup per output channel.  Thread t owns the 3x3 kernels t, t + G, t + 2G, t + 3G
-// (G = cin / 4).
-template <int MAX_THREADS, int MODE>
+// One workgroup per output channel.  Thread t owns the KPT 3x3 kernels t, t + G, t + 2G, ...
+// (G = cin / KPT); KPT is 4 for wide layers and 2 or 1 for narrow ones, so that the waves
+// stay full.
+template <int MAX_THREADS, int MODE, int KPT>
 __global__ void __launch_bounds__(MAX_THREADS) squant_channel_k9(LaunchArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];  // 9*N bytes of codes
   __shared__ K9Shared sh;
@@ -215,36 +215,39 @@ __global__ void __launch_bounds__(MAX_THREADS) squant_channel_k9(LaunchArgs a) {
 
   int m;
   const TensorDesc d = locate(a, blockIdx.x, m);
-  const int N = d.N, G = N >> 2;
-  const int L = 9 * N, nvec = 9 * G;  // nvec = L / 4 dwords of codes
+  const int N = d.N, G = N / KPT;
+  const int L = 9 * N, nvec = L >> 2;  // dwords of codes (cin % 4 == 0)
   const bool active = tid < G;
   const int t = active ? tid : 0;  // idle threads shadow thread 0's loads and write nothing
   const float* src = d.w + (size_t)m * L;
-  float w[36];
+  float w[9 * KPT];
 #pragma unroll
-  for (int q = 0; q < 4; ++q) k9_load_kernel(w, q, src + (size_t)q * (9 * G), 9u * (uint32_t)t);
+  for (int q = 0; q < KPT; ++q) k9_load_kernel(w, q, src + (size_t)q * (9 * G), 9u * (uint32_t)t);
   if (kChannelStage) select_reset(sh.sel);  // before the first barrier
 
   float amax = 0.0f;
 #pragma unroll
-  for (int j = 0; j < 36; j += 2) amax = fmaxf(fmaxf(amax, fabsf(w[j])), fabsf(w[j + 1]));
+  for (int j = 0; j + 1 < 9 * KPT; j += 2) amax = fmaxf(fmaxf(amax, fabsf(w[j])), fabsf(w[j + 1]));
+  if ((9 * KPT) & 1) amax = fmaxf(amax, fabsf(w[9 * KPT - 1]));
   amax = block_max_dpp1(amax, sh.red_f);
   const float s = amax > 0.0f ? amax / qmaxf : 1.0f;
   if (tid == 0) d.scales[m] = s;
 
   int32_t esum = 0;
-  uint32_t cv[4] = {kNoCandidate, kNoCandidate, kNoCandidate, kNoCandidate};
-  int ci[4] = {0, 0, 0, 0};
+  uint32_t cv[KPT];
+  int ci[KPT];
+#pragma unroll
+  for (int q = 0; q < KPT; ++q) { cv[q] = kNoCandidate; ci[q] = 0; }
   uint32_t zero = 0;
   if (active) {
     if (amax >= 0x1p-60f && amax <= 0x1p60f) {  // uniform over the workgroup
-      k9_solve4<true, MODE>(w, s, 1.0f / s, qmaxf, code8, t, G, esum, cv, ci, zero);
+      k9_solve_all<KPT, true, MODE>(w, s, 1.0f / s, qmaxf, code8, t, G, esum, cv, ci, zero);
     } else {
-      k9_solve4<false, MODE>(w, s, 0.0f, qmaxf, code8, t, G, esum, cv, ci, zero);
+      k9_solve_all<KPT, false, MODE>(w, s, 0.0f, qmaxf, code8, t, G, esum, cv, ci, zero);
     }
     if (kChannelStage && zero != 0) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
+      for (int q = 0; q < KPT; ++q)
         if (zero & (1u << q)) {
           const int2 z = k9_zero_sum_candidate(src + 9 * (t + q * G), s, qmaxf);
           cv[q] = candidate_word(z.x);
@@ -257,16 +260,17 @@ __global__ void __launch_bounds__(MAX_THREADS) squant_channel_k9(LaunchArgs a) {
     // publishes the codes, the partial sums and the histogram
     if (active) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) count_candidate(sh.sel, cv[q]);
+      for (int q = 0; q < KPT; ++q) count_candidate(sh.sel, cv[q]);
     }
     const int64_t ec = block_sum_dpp1(esum, sh.red_i);
     const int sgn = sign_of(ec);
     const int64_t kc = flips_for(ec < 0 ? -ec : ec);
     if (kc > 0) {
-      const int cpos[4] = {9 * t + ci[0], 9 * (t + G) + ci[1], 9 * (t + 2 * G) + ci[2],
-                           9 * (t + 3 * G) + ci[3]};
-      channel_stage<4>(cv, cpos, tid, G, sgn, (uint32_t)(kc > N ? N : kc),
-                       reinterpret_cast<uint32_t*>(smem), sh.sel);
+      int cpos[KPT], cn[KPT];
+#pragma unroll
+      for (int q = 0; q < KPT; ++q) { cn[q] = t + q * G; cpos[q] = 9 * cn[q] + ci[q]; }
+      channel_stage<KPT, 1>(cv, cpos, cn, sgn, (uint32_t)(kc > N ? N : kc),
+                            reinterpret_cast<uint32_t*>(smem), sh.sel);
     }
   }
   __syncthreads();

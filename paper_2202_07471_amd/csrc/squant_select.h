@@ -109,16 +109,17 @@ __device__ __forceinline__ uint32_t scan_histogram_top(const uint32_t* hist, uin
 }
 
 // Every thread holds NC candidates: the candidate word cw[q], the byte offset pos[q] of the
-// candidate element inside the channel's biased codes in LDS, and the kernel index
-// n0 + q * nstride (nstride = 1: a thread owns consecutive kernels; nstride = number of
-// kernel-carrying threads: thread t owns kernels t, t + nstride, ...).
+// candidate element inside the channel's biased codes in LDS, and the kernel index nidx[q]
+// that breaks ties (lowest first).  The candidates come in NC / PER_ROUND rounds: within a
+// round a thread's PER_ROUND kernel indices are consecutive, ascend with q, and ascend
+// from thread to thread; every index of round r is below every index of round r + 1.
 // Flips the selected candidates' codes one step against the channel sum (code -= sgn).
 // Must be called by all threads of the workgroup, after every candidate has been counted
 // (count_candidate) and a workgroup barrier has passed.
-template <int NC>
-__device__ __forceinline__ void channel_stage(const uint32_t (&cw)[NC], const int (&pos)[NC], int n0,
-                                              int nstride, int sgn, uint32_t need, uint32_t* code32,
-                                              SelectShared& sh) {
+template <int NC, int PER_ROUND>
+__device__ __forceinline__ void channel_stage(const uint32_t (&cw)[NC], const int (&pos)[NC],
+                                              const int (&nidx)[NC], int sgn, uint32_t need,
+                                              uint32_t* code32, SelectShared& sh) {
   const uint32_t half = sgn < 0 ? 256u : 0u;
   uint32_t key[NC];
   bool live[NC];  // eligible and still undecided
@@ -182,7 +183,7 @@ __device__ __forceinline__ void channel_stage(const uint32_t (&cw)[NC], const in
       if (live[q]) {
         const uint32_t slot = atomicAdd(&sh.list_count, 1u);
         sh.list_key[slot] = key[q];
-        sh.list_n[slot] = (uint32_t)(n0 + q * nstride);
+        sh.list_n[slot] = (uint32_t)nidx[q];
       }
     __syncthreads();
 #pragma unroll
@@ -191,24 +192,23 @@ __device__ __forceinline__ void channel_stage(const uint32_t (&cw)[NC], const in
         uint32_t rank = 0;
         for (uint32_t e = 0; e < count; ++e) {
           const uint32_t ek = sh.list_key[e], en = sh.list_n[e];
-          rank += (ek > key[q] || (ek == key[q] && en < (uint32_t)(n0 + q * nstride))) ? 1u : 0u;
+          rank += (ek > key[q] || (ek == key[q] && en < (uint32_t)nidx[q])) ? 1u : 0u;
         }
         if (rank < need) flip_code(code32, pos[q], sgn);
       }
     return;
   }
   // more than kListCap keys equal in all their bits: the lowest kernel indices flip.
-  // Kernel order is thread order within one q (nstride > 1) or thread order over all q
-  // (nstride = 1), so exclusive prefix counts over the threads rank them.
+  // Inside a round kernel order is thread order, so an exclusive prefix count over the
+  // threads ranks them; the rounds are taken one after the other.
   const int lane = threadIdx.x & (kWave - 1), wid = threadIdx.x / kWave;
   const int nw = (blockDim.x + kWave - 1) / kWave;
-  const int rounds = nstride == 1 ? 1 : NC;
   uint32_t done = 0;  // live keys with a lower kernel index, counted in earlier rounds
-  for (int round = 0; round < rounds; ++round) {
+  for (int round = 0; round < NC / PER_ROUND; ++round) {
     uint32_t mine = 0;
 #pragma unroll
     for (int q = 0; q < NC; ++q)
-      if (nstride == 1 || q == round) mine += live[q] ? 1u : 0u;
+      if (q / PER_ROUND == round) mine += live[q] ? 1u : 0u;
     const uint32_t incl = wave_prefix_sum(mine);
     __syncthreads();
     if (lane == kWave - 1) sh.wave_cnt[wid] = incl;
@@ -221,7 +221,7 @@ __device__ __forceinline__ void channel_stage(const uint32_t (&cw)[NC], const in
     }
 #pragma unroll
     for (int q = 0; q < NC; ++q)
-      if ((nstride == 1 || q == round) && live[q]) {
+      if (q / PER_ROUND == round && live[q]) {
         if (base < need) flip_code(code32, pos[q], sgn);
         ++base;
       }
