@@ -121,7 +121,10 @@ Plan plan_tensor(const void* w, const void* codes, int64_t N, int64_t K, int lds
     return Plan{variant, threads, round_up((size_t)9 * N, 16)};  // LDS: the channel's int8 codes
   }
   if (K == 1 && (N & 3) == 0 && N <= 32768 && aligned) {
-    const int nv = N <= 1024 ? 1 : N <= 2048 ? 2 : N <= 4096 ? 4 : 8;
+    // 16-byte vectors per thread: one full wave per channel while that takes at most four
+    // per thread (measured best), then up to 256 threads with four, then eight
+    const int64_t nvec = N / 4;
+    const int nv = nvec <= 64 ? 1 : nvec <= 128 ? 2 : nvec <= 1024 ? 4 : 8;
     const int threads = (int)round_up(((size_t)N / 4 + nv - 1) / nv, kWave);
     const int variant = nv == 1 ? kK1x1 : nv == 2 ? kK1x2 : nv == 4 ? kK1x4 : kK1x8;
     return Plan{variant, threads, round_up((size_t)N, 16)};  // LDS: the channel's int8 codes
@@ -356,6 +359,6 @@ const char* squant_status_string(int status) {
   }
 }
 
-int squant_version(void) { return 112; }
+int squant_version(void) { return 113; }
 
 }  // extern "C"

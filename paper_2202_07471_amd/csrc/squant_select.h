@@ -19,7 +19,13 @@
 
 namespace squant {
 
-constexpr int kListCap = 128;
+constexpr int kListCap = 128;  // capacity of the ranking list
+#ifndef SQ_TUNE_LIST_RANK
+#define SQ_TUNE_LIST_RANK 16
+#endif
+constexpr int kListRank = SQ_TUNE_LIST_RANK;  // rank through the list up to this many keys; above
+                                              // it another histogram pass is cheaper than the
+                                              // quadratic ranking
 constexpr int kHistDummy = 512;  // bin of "no candidate"
 constexpr uint32_t kNoDigit = 0xFFFFFFFFu;
 
@@ -149,7 +155,7 @@ __device__ __forceinline__ void channel_stage(const uint32_t (&cw)[NC], const in
 
   // ---- a crowded digit: histogram passes over the lower bits (from bit 7, then bit 0) ----
   int shift = 15;
-  while (count > (uint32_t)kListCap && shift > 0) {
+  while (count > (uint32_t)kListRank && count != need && shift > 0) {
     shift = shift == 15 ? 7 : 0;
     __syncthreads();  // every wave has finished reading the histogram
     for (int b = threadIdx.x; b < 256; b += blockDim.x) sh.hist[b] = 0;
