@@ -123,6 +123,19 @@ __device__ __forceinline__ int64_t wave_sum_dpp(int32_t v) {
          (int64_t)__builtin_amdgcn_readlane(v, 32) + (int64_t)__builtin_amdgcn_readlane(v, 48);
 }
 
+// Running maximum over the lanes of a wave: lane 63 ends up with the wave's maximum (same
+// DPP steps as a prefix sum).
+__device__ __forceinline__ uint32_t wave_prefix_max_u32(uint32_t x) {
+  int v = (int)x;
+  v = (int)max((uint32_t)v, (uint32_t)__builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true));
+  v = (int)max((uint32_t)v, (uint32_t)__builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true));
+  v = (int)max((uint32_t)v, (uint32_t)__builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true));
+  v = (int)max((uint32_t)v, (uint32_t)__builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true));
+  v = (int)max((uint32_t)v, (uint32_t)__builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false));
+  v = (int)max((uint32_t)v, (uint32_t)__builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false));
+  return (uint32_t)v;
+}
+
 // Workgroup-wide versions: every thread returns the result.  `slot` holds >= 16 entries.
 __device__ __forceinline__ float block_max_dpp(float v, float* slot) {
   v = wave_max_dpp(v);

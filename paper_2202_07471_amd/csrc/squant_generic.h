@@ -99,9 +99,130 @@ __device__ void apply_channel_flips(const int32_t* cand, const int32_t* cidx, in
 }
 
 // ---------------------------------------------------------------------------
-// Generic kernel: any (N, K) whose channel fits in LDS.  One thread per kh*kw
-// kernel in the SQuant-K stage, Q23 perturbations and int8 codes held in LDS.
+// SQuant-K and the candidate update for ONE kernel by ONE wave (large kh*kw, e.g. a
+// 7x7 stem): element i sits with lane i % 64.  The k-th largest same-sign |p| is
+// found by a wavefront-level radix select, one ballot + population count per key bit
+// from the top (Algorithm 2's top-k); elements above it flip, and of those equal to it
+// the lowest indices (ballot prefix ranks).  Everything the wave decides is uniform.
+//   pk, ck   the kernel's K perturbations (Q23) and codes in LDS, updated in place
+//   returns  the kernel's perturbation sum after the flips; cv / ci = Algorithm 3 candidate
 // ---------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t same_sign_key(int32_t p, int sgn) {
+  const int32_t a = sgn > 0 ? p : -p;
+  return a > 0 ? (uint32_t)a : 0u;  // 0 = not eligible
+}
+
+__device__ int64_t kernel_stage_wave(int32_t* pk, int8_t* ck, int K, int mode, int32_t& cv,
+                                     int32_t& ci) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const unsigned long long below = (1ull << lane) - 1ull;
+  int64_t part = 0;
+  for (int i = lane; i < K; i += kWave) part += pk[i];
+  int64_t e = wave_sum(part);
+  const int sgn = sign_of(e);
+  const int64_t A = e < 0 ? -e : e;
+  const uint32_t k = (mode == SQUANT_MODE_EC) ? 0u : (uint32_t)flips_for(A);
+  cv = 0;
+  ci = 0;
+  if (sgn == 0) {  // nothing masked: largest |p| of either sign, lowest index
+    uint32_t best = 0;
+    for (int i = lane; i < K; i += kWave) {
+      const int32_t p = pk[i];
+      best = max(best, (uint32_t)(p < 0 ? -p : p));
+    }
+    best = (uint32_t)__builtin_amdgcn_readlane((int)wave_prefix_max_u32(best), kWave - 1);
+    if (best != 0) {
+      for (int base = 0; base < K; base += kWave) {
+        const int i = base + lane;
+        const int32_t p = i < K ? pk[i] : 0;
+        const unsigned long long hit = __ballot(i < K && (uint32_t)(p < 0 ? -p : p) == best);
+        if (hit) {
+          const int l = __builtin_ctzll(hit);
+          ci = base + l;
+          cv = __builtin_amdgcn_readlane(p, l);
+          break;
+        }
+      }
+    }
+    return e;
+  }
+
+  uint32_t T = 0xFFFFFFFFu;  // key of the k-th largest same-sign element (nothing flips if k = 0)
+  uint32_t take_eq = 0;      // how many of the elements with key == T flip
+  if (k > 0) {
+    uint32_t prefix = 0, need = k;
+    for (int b = 22; b >= 0; --b) {
+      const uint32_t want = (prefix << 1) | 1u;
+      uint32_t cnt = 0;
+      for (int base = 0; base < K; base += kWave) {
+        const int i = base + lane;
+        const uint32_t key = i < K ? same_sign_key(pk[i], sgn) : 0u;
+        cnt += (uint32_t)__popcll(__ballot(key != 0 && (key >> b) == want));
+      }
+      if (cnt >= need) prefix = want; else { need -= cnt; prefix <<= 1; }
+    }
+    T = prefix;
+    take_eq = need;
+  }
+
+  // flip pass; remembers the last flipped element (over SQuant) and the first un-flipped
+  // element equal to T, if any (under SQuant)
+  uint32_t eq_before = 0;
+  int over_i = -1, under_i = -1;
+  for (int base = 0; base < K && k > 0; base += kWave) {
+    const int i = base + lane;
+    const int32_t p = i < K ? pk[i] : 0;
+    const uint32_t key = i < K ? same_sign_key(p, sgn) : 0u;
+    const bool eq = key != 0 && key == T;
+    const unsigned long long eqmask = __ballot(eq);
+    const uint32_t rank = eq_before + (uint32_t)__popcll(eqmask & below);
+    const bool take = key != 0 && (key > T || (eq && rank < take_eq));
+    if (take) {
+      pk[i] = p - sgn * kOne;
+      ck[i] = (int8_t)(ck[i] - sgn);
+    }
+    const unsigned long long last = __ballot(eq && rank == take_eq - 1);
+    if (last) over_i = base + __builtin_ctzll(last);
+    const unsigned long long next = __ballot(eq && rank == take_eq);
+    if (next && under_i < 0) under_i = base + __builtin_ctzll(next);
+    eq_before += (uint32_t)__popcll(eqmask);
+  }
+  e -= (int64_t)sgn * (int64_t)k * kOne;
+
+  if ((int64_t)k * kOne > A) {  // over SQuant: the last flipped element, post-flip value
+    if (over_i >= 0) { ci = over_i; cv = pk[over_i]; }
+    return e;
+  }
+  // under SQuant: the first un-flipped same-sign element
+  if (under_i >= 0) { ci = under_i; cv = pk[under_i]; return e; }
+  uint32_t best = 0;  // largest same-sign key below T (all keys >= T have flipped sign by now)
+  for (int i = lane; i < K; i += kWave) {
+    const uint32_t key = same_sign_key(pk[i], sgn);
+    if (key < T) best = max(best, key);
+  }
+  best = (uint32_t)__builtin_amdgcn_readlane((int)wave_prefix_max_u32(best), kWave - 1);
+  if (best != 0) {
+    for (int base = 0; base < K; base += kWave) {
+      const int i = base + lane;
+      const int32_t p = i < K ? pk[i] : 0;
+      const unsigned long long hit = __ballot(i < K && same_sign_key(p, sgn) == best);
+      if (hit) {
+        const int l = __builtin_ctzll(hit);
+        ci = base + l;
+        cv = __builtin_amdgcn_readlane(p, l);
+        break;
+      }
+    }
+  }
+  return e;
+}
+
+// ---------------------------------------------------------------------------
+// Generic kernel: any (N, K) whose channel fits in LDS.  Q23 perturbations and int8
+// codes are held in LDS; the SQuant-K stage takes one thread per kh*kw kernel for small
+// kernels and one wave per kernel from kWaveKernelMinK elements on.
+// ---------------------------------------------------------------------------
+constexpr int kWaveKernelMinK = 32;
 
 __global__ void __launch_bounds__(1024) squant_channel_generic(LaunchArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -151,7 +272,20 @@ __global__ void __launch_bounds__(1024) squant_channel_generic(LaunchArgs a) {
   __syncthreads();
 
   if (a.mode != SQUANT_MODE_E) {
-    if (K > 1) {
+    if (K >= kWaveKernelMinK) {
+      // ---- SQuant-K and the candidate update, one wave per kernel ----
+      esum = 0;
+      const int wid = tid / kWave, nw = T / kWave;
+      for (int n = wid; n < N; n += nw) {
+        int32_t cv, ci;
+        const int64_t e = kernel_stage_wave(buf + n * K, code + n * K, K, a.mode, cv, ci);
+        if ((tid & (kWave - 1)) == 0) {
+          esum += e;
+          cand[n] = cv;
+          cidx[n] = ci;
+        }
+      }
+    } else if (K > 1) {
       // ---- SQuant-K and the candidate update, one thread per kernel ----
       esum = 0;
       for (int n = tid; n < N; n += T) {

@@ -58,7 +58,7 @@ size_t generic_lds_bytes(int64_t N, int64_t K) {
 
 int generic_threads(int64_t N, int64_t K) {
   const int64_t L = N * K;
-  int64_t want = (K == 1) ? (L + 7) / 8 : N;
+  int64_t want = (K == 1) ? (L + 7) / 8 : (K >= kWaveKernelMinK) ? N * kWave : N;
   want = (want + kWave - 1) / kWave * kWave;
   return (int)std::min<int64_t>(512, std::max<int64_t>(kWave, want));
 }
@@ -277,21 +277,20 @@ int squant_quantize_batched(const squant_tensor_t* h_tensors, int32_t n_tensors,
   hipStream_t st = (hipStream_t)stream;
   TensorDesc* table = static_cast<TensorDesc*>(d_workspace);
   const int qmax = (1 << (bits - 1)) - 1;
-  // descriptor tables of all groups first, then the solver kernels back to back
-  size_t offset = 0;
-  for (const auto& g : groups) {
-    for (size_t c0 = 0; c0 < g.t.size(); c0 += kDescChunk) {
-      DescChunk chunk{};
-      const int cnt = (int)std::min<size_t>(kDescChunk, g.t.size() - c0);
-      for (int i = 0; i < cnt; ++i) chunk.t[i] = g.t[c0 + i];
-      hipLaunchKernelGGL(write_table, dim3(1), dim3(kDescChunk), 0, st, chunk, cnt,
-                         table + offset + c0);
-      if (hipGetLastError() != hipSuccess) return SQUANT_ERR_DEVICE;
-    }
-    offset += g.t.size();
+  // the descriptors of all groups, group after group, go up first (kDescChunk per writer
+  // launch), then the solver kernels follow back to back
+  std::vector<TensorDesc> all;
+  all.reserve((size_t)n_tensors);
+  for (const auto& g : groups) all.insert(all.end(), g.t.begin(), g.t.end());
+  for (size_t c0 = 0; c0 < all.size(); c0 += kDescChunk) {
+    DescChunk chunk{};
+    const int cnt = (int)std::min<size_t>(kDescChunk, all.size() - c0);
+    for (int i = 0; i < cnt; ++i) chunk.t[i] = all[c0 + i];
+    hipLaunchKernelGGL(write_table, dim3(1), dim3(kDescChunk), 0, st, chunk, cnt, table + c0);
+    if (hipGetLastError() != hipSuccess) return SQUANT_ERR_DEVICE;
   }
   timer_mark(true, st);
-  offset = 0;
+  size_t offset = 0;
   for (const auto& g : groups) {
     if (int rc = launch_group(g, table + offset, qmax, (int)mode, st)) return rc;
     offset += g.t.size();
@@ -359,6 +358,6 @@ const char* squant_status_string(int status) {
   }
 }
 
-int squant_version(void) { return 113; }
+int squant_version(void) { return 114; }
 
 }  // extern "C"
