@@ -62,6 +62,11 @@ def main() -> int:
                     help="cout,cin,kh,kw: replace the workload by --count He-normal tensors of this shape "
                          "(exploration only; not the headline configuration)")
     ap.add_argument("--count", type=int, default=1)
+    ap.add_argument("--output", default="int8", choices=["int8", "int4", "f32"],
+                    help="what the solver writes per weight: int8 codes (headline), packed 4-bit "
+                         "codes, or dequantised float32")
+    ap.add_argument("--wtype", default="f32", choices=["f32", "f16", "bf16"],
+                    help="element type the weights are handed over in (headline: f32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for HBM byte counters)")
@@ -101,14 +106,17 @@ def main() -> int:
     host_sample, dws = [], []
     for s in specs:
         w = synth.generate(s)
-        dws.append(torch.from_numpy(w).to(dev))
+        dw = torch.from_numpy(w).to(dev)
+        if args.wtype != "f32":        # the generator's weights rounded once to the 16-bit type
+            dw = dw.to(torch.float16 if args.wtype == "f16" else torch.bfloat16)
+        dws.append(dw)
         if s.index < cpu_sample_tensors:
-            host_sample.append(w)
+            host_sample.append(w if args.wtype == "f32" else dw.float().cpu().numpy())
     torch.cuda.synchronize()
     log(f"[bench] generated + uploaded in {time.time() - t0:.1f} s "
         f"({sum(s.dist == 'student_t3' for s in specs)} Student-t tensors)")
 
-    plan = sq.BatchPlan(dws)
+    plan = sq.BatchPlan(dws, sq.OUTPUTS[args.output])
     mode = sq.MODES[args.mode]
     if args.calibrate_copy:
         a_ = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -137,9 +145,14 @@ def main() -> int:
     ms_per_step = elapsed * 1e3 / max(args.steps, 1)
     value = n_params * args.steps / elapsed / 1e9
     k_avg_ms = float(np.mean(kernel_ms))
-    algo_bytes = 5.0 * n_params + 4.0 * n_channels      # 4 B read + 1 B written per weight, 4 B per scale
+    # bytes read + written per weight (4 + 1 in the headline configuration), 4 B per scale
+    in_bytes = {"f32": 4.0, "f16": 2.0, "bf16": 2.0}[args.wtype]
+    out_bytes = {"int8": 1.0, "int4": 0.5, "f32": 4.0}[args.output]
+    algo_bytes = (in_bytes + out_bytes) * n_params + 4.0 * n_channels
     achieved = algo_bytes / (k_avg_ms * 1e-3) / 1e9
-    traffic = load_traffic(sq.squant_version()) if args.workload == "c5" and args.tensors is None else None
+    headline_io = args.output == "int8" and args.wtype == "f32"
+    traffic = (load_traffic(sq.squant_version())
+               if args.workload == "c5" and args.tensors is None and headline_io else None)
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "kernel": "squant solver kernel(s) of the batched call",
@@ -172,6 +185,10 @@ def main() -> int:
         for i, (rc, rs) in enumerate(ref):
             gc = plan.codes[i].cpu().numpy()
             gs = plan.scales[i].cpu().numpy()
+            if args.output == "int4":
+                rc = oracle.pack_int4(rc)
+            elif args.output == "f32":
+                rc, gc = oracle.dequantize(rc, rs).view(np.uint32), gc.view(np.uint32)
             mism += int((gc != rc).sum()) + int((gs.view(np.uint32) != rs.view(np.uint32)).sum())
         cpu_baseline = {"value": round(sample_params / cpu_s / 1e9, 5), "unit": "Gparams/s",
                         "cores": threads, "kind": "oracle",
@@ -191,6 +208,7 @@ def main() -> int:
         "scaling": "weak", "vs_baseline": None, "dtype": "f32+int32",
         "data": "synthetic",
         "config": {"workload": desc if args.shape else f"{args.workload}: {desc}", "bits": args.bits, "mode": args.mode,
+                   "weight_type": args.wtype, "output": args.output,
                    "tensors": len(specs), "weights": n_params, "output_channels": n_channels,
                    "seed": synth.DEFAULT_SEED},
         "roofline": roofline, "cpu_baseline": cpu_baseline,

@@ -63,13 +63,39 @@ typedef enum {
   SQUANT_ERR_MODE = 4,      /* unknown mode */
   SQUANT_ERR_WORKSPACE = 5, /* workspace missing or too small */
   SQUANT_ERR_DEVICE = 6,    /* a HIP call failed */
-  SQUANT_ERR_UNSUPPORTED = 7 /* one output channel (cin*kh*kw) exceeds what one workgroup's LDS holds */
+  SQUANT_ERR_UNSUPPORTED = 7, /* one output channel (cin*kh*kw) exceeds what one workgroup's LDS holds */
+  SQUANT_ERR_FORMAT = 8     /* unknown weight or output type, or a buffer misaligned for its element type */
 } squant_status_t;
+
+/* What the solver writes for each weight (squant_quantize_ex).  Section 2.2 defines the
+ * quantised weight as an integer code times the scale and Algorithm 1 returns that
+ * product; a deployment stores the codes, and at 4 bits and below two of them fit a byte.
+ *   INT8  one int8 code per weight, the tensor's own layout.
+ *   INT4  bits <= 4 only.  Output channel m occupies bytes [m*R, (m+1)*R) with
+ *         R = (cin*kh*kw + 1) / 2; byte j of a row holds element 2j in its low nibble and
+ *         element 2j+1 in its high nibble, each the code's 4-bit two's complement; the
+ *         unused high nibble of an odd row's last byte is 0.
+ *   F32   the dequantised weight (float)code * scales[m] (one binary32 multiply), the
+ *         tensor's own layout. */
+typedef enum {
+  SQUANT_OUT_INT8 = 0,
+  SQUANT_OUT_INT4 = 1,
+  SQUANT_OUT_F32 = 2
+} squant_output_t;
+
+/* Element type of the weights handed in.  The solver's arithmetic is binary32 whatever the
+ * type: binary16 and bfloat16 weights are widened exactly first. */
+typedef enum {
+  SQUANT_W_F32 = 0,
+  SQUANT_W_F16 = 1,  /* IEEE binary16 */
+  SQUANT_W_BF16 = 2  /* bfloat16: the upper 16 bits of a binary32 */
+} squant_wtype_t;
 
 /* One weight tensor of a batched call. */
 typedef struct {
-  const float* w;            /* in : device, cout*cin*kh*kw binary32 */
-  int8_t* codes;             /* out: device, same element count and layout, values in [-qmax, qmax] */
+  const void* w;             /* in : device, cout*cin*kh*kw weights (binary32 unless the call says otherwise) */
+  void* codes;               /* out: device; int8 codes in [-qmax, qmax], same count and layout as w,
+                                unless the call names another squant_output_t */
   float* scales;             /* out: device, cout binary32 */
   int32_t cout, cin, kh, kw;
 } squant_tensor_t;
@@ -92,6 +118,24 @@ size_t squant_batched_workspace_bytes(int32_t n_tensors);
 int squant_quantize_batched(const squant_tensor_t* h_tensors, int32_t n_tensors, int32_t bits,
                             squant_mode_t mode, void* d_workspace, size_t workspace_bytes,
                             void* stream);
+
+/* Bytes of the output buffer of one tensor in the given format (0 on invalid arguments). */
+size_t squant_output_bytes(int32_t cout, int32_t cin, int32_t kh, int32_t kw, squant_output_t output);
+
+/* squant_quantize / squant_quantize_batched with the weight type and the output format
+ * chosen by the caller (Algorithm 1; Section 2.2 for the dequantised form).  d_w holds
+ * cout*cin*kh*kw elements of `wtype`, aligned to their size; d_out is a buffer of
+ * squant_output_bytes() bytes, aligned to 4 bytes for F32 output; in the batched call the
+ * `w` and `codes` members of each descriptor play these two roles and every tensor shares
+ * wtype and output.  SQUANT_OUT_INT4 needs bits <= 4 (SQUANT_ERR_BITS otherwise).  With
+ * SQUANT_W_F32 and SQUANT_OUT_INT8 the calls are the plain ones above. */
+int squant_quantize_ex(const void* d_w, squant_wtype_t wtype, int32_t cout, int32_t cin,
+                       int32_t kh, int32_t kw, int32_t bits, squant_mode_t mode,
+                       squant_output_t output, void* d_out, float* d_scales, void* stream);
+int squant_quantize_batched_ex(const squant_tensor_t* h_tensors, int32_t n_tensors,
+                               squant_wtype_t wtype, int32_t bits, squant_mode_t mode,
+                               squant_output_t output, void* d_workspace, size_t workspace_bytes,
+                               void* stream);
 
 /* Largest cin*kh*kw one output channel may have (device dependent; 0 on error). */
 int64_t squant_max_channel_elems(int32_t kh, int32_t kw);

@@ -42,6 +42,14 @@ def lib():
         L.squant_oracle_quantize.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp]
         L.squant_oracle_quantize_mt.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp, i32]
         L.squant_oracle_quantize_trace.argtypes = [vp, i32, i32, i32, i32, i32, i32, vp, vp] + [vp] * 7
+        i64 = ctypes.c_int64
+        L.squant_oracle_pack_int4.argtypes = [vp, i64, i64, vp]
+        L.squant_oracle_dequantize.argtypes = [vp, vp, i64, i64, vp]
+        L.squant_oracle_widen_f16.argtypes = [vp, i64, vp]
+        L.squant_oracle_widen_bf16.argtypes = [vp, i64, vp]
+        for f in (L.squant_oracle_pack_int4, L.squant_oracle_dequantize,
+                  L.squant_oracle_widen_f16, L.squant_oracle_widen_bf16):
+            f.restype = ctypes.c_int
         for f in (L.squant_oracle_quantize, L.squant_oracle_quantize_mt,
                   L.squant_oracle_quantize_trace, L.squant_oracle_hardware_threads):
             f.restype = ctypes.c_int
@@ -102,3 +110,40 @@ def quantize_trace(w, bits: int, mode: int = MODE_EKC):
 
 def hardware_threads() -> int:
     return int(lib().squant_oracle_hardware_threads())
+
+
+def pack_int4(codes):
+    """codes int8 [cout, ...] with |code| <= 7 -> uint8 [cout, (len + 1) // 2], two per byte."""
+    c = np.ascontiguousarray(codes, dtype=np.int8)
+    cout = c.shape[0]
+    n = c.size // cout
+    out = np.empty((cout, (n + 1) // 2), dtype=np.uint8)
+    rc = lib().squant_oracle_pack_int4(c.ctypes.data, cout, n, out.ctypes.data)
+    if rc != 0:
+        raise ValueError(f"squant_oracle_pack_int4 failed with status {rc}")
+    return out
+
+
+def dequantize(codes, scales):
+    """code * scale of its output channel, float32, same shape as codes."""
+    c = np.ascontiguousarray(codes, dtype=np.int8)
+    s = np.ascontiguousarray(scales, dtype=np.float32)
+    cout = c.shape[0]
+    assert s.shape == (cout,)
+    out = np.empty(c.shape, dtype=np.float32)
+    rc = lib().squant_oracle_dequantize(c.ctypes.data, s.ctypes.data, cout, c.size // cout,
+                                        out.ctypes.data)
+    if rc != 0:
+        raise ValueError(f"squant_oracle_dequantize failed with status {rc}")
+    return out
+
+
+def widen(bits16, wtype: str):
+    """uint16 bit patterns of binary16 ("f16") or bfloat16 ("bf16") weights -> float32."""
+    h = np.ascontiguousarray(bits16, dtype=np.uint16)
+    out = np.empty(h.shape, dtype=np.float32)
+    fn = {"f16": lib().squant_oracle_widen_f16, "bf16": lib().squant_oracle_widen_bf16}[wtype]
+    rc = fn(h.ctypes.data, h.size, out.ctypes.data)
+    if rc != 0:
+        raise ValueError(f"widen failed with status {rc}")
+    return out

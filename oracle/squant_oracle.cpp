@@ -263,4 +263,70 @@ int squant_oracle_hardware_threads(void) {
   return n ? (int)n : 1;
 }
 
+// ---- output forms and input types beside the int8 codes of binary32 weights ----
+
+// Two 4-bit codes to a byte (needs |code| <= 7, i.e. bits <= 4).  Row m of the output has
+// (len + 1) / 2 bytes; byte j holds element 2j in its low nibble and element 2j + 1 in its
+// high nibble, each as 4-bit two's complement; a missing last element leaves 0.
+// Returns 0, or 1 null pointer / 2 bad shape / 3 a code outside [-8, 7].
+int squant_oracle_pack_int4(const int8_t* codes, int64_t cout, int64_t len, uint8_t* packed) {
+  if (!codes || !packed) return 1;
+  if (cout <= 0 || len <= 0) return 2;
+  const int64_t row = (len + 1) / 2;
+  for (int64_t m = 0; m < cout; ++m)
+    for (int64_t j = 0; j < row; ++j) {
+      int nib[2] = {0, 0};
+      for (int h = 0; h < 2; ++h) {
+        const int64_t i = 2 * j + h;
+        if (i >= len) continue;
+        const int c = codes[m * len + i];
+        if (c < -8 || c > 7) return 3;
+        nib[h] = c < 0 ? c + 16 : c;  // two's complement in 4 bits
+      }
+      packed[m * row + j] = (uint8_t)(nib[0] + 16 * nib[1]);
+    }
+  return 0;
+}
+
+// The quantised weight of Section 2.2, code * scale of its output channel, as the one
+// binary32 product (what Algorithm 1 returns).
+int squant_oracle_dequantize(const int8_t* codes, const float* scales, int64_t cout, int64_t len,
+                             float* out) {
+  if (!codes || !scales || !out) return 1;
+  if (cout <= 0 || len <= 0) return 2;
+  for (int64_t m = 0; m < cout; ++m)
+    for (int64_t i = 0; i < len; ++i) out[m * len + i] = (float)codes[m * len + i] * scales[m];
+  return 0;
+}
+
+// IEEE binary16 (1 sign, 5 exponent, 10 fraction bits) to binary32, exactly, from the
+// format's definition: (-1)^s * 2^(e-15) * (1 + f/1024), subnormals 2^-14 * f/1024.
+int squant_oracle_widen_f16(const uint16_t* h, int64_t n, float* out) {
+  if (!h || !out) return 1;
+  for (int64_t i = 0; i < n; ++i) {
+    const int sign = h[i] >> 15, e = (h[i] >> 10) & 31, f = h[i] & 1023;
+    double v;
+    if (e == 31) v = f ? (double)NAN : (double)INFINITY;
+    else if (e == 0) v = std::ldexp((double)f, -24);
+    else v = std::ldexp(1024.0 + f, e - 25);
+    out[i] = (float)(sign ? -v : v);
+  }
+  return 0;
+}
+
+// bfloat16 (1 sign, 8 exponent, 7 fraction bits: a binary32 cut after 16 bits) to binary32,
+// from the same kind of definition: (-1)^s * 2^(e-127) * (1 + f/128), subnormals 2^-126 * f/128.
+int squant_oracle_widen_bf16(const uint16_t* h, int64_t n, float* out) {
+  if (!h || !out) return 1;
+  for (int64_t i = 0; i < n; ++i) {
+    const int sign = h[i] >> 15, e = (h[i] >> 7) & 255, f = h[i] & 127;
+    double v;
+    if (e == 255) v = f ? (double)NAN : (double)INFINITY;
+    else if (e == 0) v = std::ldexp((double)f, -133);
+    else v = std::ldexp(128.0 + f, e - 134);
+    out[i] = (float)(sign ? -v : v);
+  }
+  return 0;
+}
+
 }  // extern "C"

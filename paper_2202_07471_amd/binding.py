@@ -16,6 +16,10 @@ LIB_PATH = os.path.join(_HERE, "libsquant_hip.so")
 
 MODE_E, MODE_EK, MODE_EKC, MODE_EC = 0, 1, 2, 3
 MODES = {"E": MODE_E, "EK": MODE_EK, "EKC": MODE_EKC, "EC": MODE_EC}
+OUT_INT8, OUT_INT4, OUT_F32 = 0, 1, 2
+OUTPUTS = {"int8": OUT_INT8, "int4": OUT_INT4, "f32": OUT_F32}
+W_F32, W_F16, W_BF16 = 0, 1, 2
+_WTYPES = {torch.float32: W_F32, torch.float16: W_F16, torch.bfloat16: W_BF16}
 
 
 class squant_tensor_t(ctypes.Structure):
@@ -50,6 +54,14 @@ def lib():
         L.squant_quantize_batched.argtypes = [ctypes.POINTER(squant_tensor_t), i32, i32,
                                               ctypes.c_int, vp, sz, vp]
         L.squant_quantize_batched.restype = ctypes.c_int
+        L.squant_output_bytes.argtypes = [i32, i32, i32, i32, ctypes.c_int]
+        L.squant_output_bytes.restype = sz
+        L.squant_quantize_ex.argtypes = [vp, ctypes.c_int, i32, i32, i32, i32, i32, ctypes.c_int,
+                                         ctypes.c_int, vp, vp, vp]
+        L.squant_quantize_ex.restype = ctypes.c_int
+        L.squant_quantize_batched_ex.argtypes = [ctypes.POINTER(squant_tensor_t), i32, ctypes.c_int,
+                                                 i32, ctypes.c_int, ctypes.c_int, vp, sz, vp]
+        L.squant_quantize_batched_ex.restype = ctypes.c_int
         L.squant_max_channel_elems.argtypes = [i32, i32]
         L.squant_max_channel_elems.restype = ctypes.c_int64
         L.squant_status_string.argtypes = [ctypes.c_int]
@@ -74,6 +86,10 @@ def squant_version() -> int:
 
 def squant_max_channel_elems(kh: int, kw: int) -> int:
     return int(lib().squant_max_channel_elems(kh, kw))
+
+
+def squant_output_bytes(cout: int, cin: int, kh: int, kw: int, output: int) -> int:
+    return int(lib().squant_output_bytes(cout, cin, kh, kw, output))
 
 
 def squant_batched_workspace_bytes(n_tensors: int) -> int:
@@ -117,6 +133,27 @@ def _check_weight(w: torch.Tensor):
         raise ValueError("weight must be a contiguous float32 tensor in device memory")
 
 
+def _wtype(w: torch.Tensor) -> int:
+    if not (w.is_cuda and w.dtype in _WTYPES and w.is_contiguous()):
+        raise ValueError("weight must be a contiguous float32, float16 or bfloat16 tensor in device memory")
+    return _WTYPES[w.dtype]
+
+
+def _new_output(shape, output: int, device) -> torch.Tensor:
+    """An output buffer of the format's shape: int8 / float32 like the weights, or uint8
+    [cout, (cin*kh*kw + 1) // 2] for packed 4-bit codes."""
+    if output == OUT_INT8:
+        return torch.empty(shape, dtype=torch.int8, device=device)
+    if output == OUT_F32:
+        return torch.empty(shape, dtype=torch.float32, device=device)
+    if output == OUT_INT4:
+        n = 1
+        for d in shape[1:]:
+            n *= d
+        return torch.empty((shape[0], (n + 1) // 2), dtype=torch.uint8, device=device)
+    raise ValueError(f"unknown output format {output}")
+
+
 def squant_quantize(w: torch.Tensor, bits: int, mode: int = MODE_EKC, codes: torch.Tensor = None,
                     scales: torch.Tensor = None, stream=None):
     """Quantize one weight tensor; returns (codes int8 like w, scales float32 [cout]).
@@ -133,20 +170,38 @@ def squant_quantize(w: torch.Tensor, bits: int, mode: int = MODE_EKC, codes: tor
     return codes, scales
 
 
+def squant_quantize_ex(w: torch.Tensor, bits: int, mode: int = MODE_EKC, output: int = OUT_INT8,
+                       out: torch.Tensor = None, scales: torch.Tensor = None, stream=None):
+    """squant_quantize for float32 / float16 / bfloat16 weights with the output format chosen:
+    returns (out, scales), out being int8 codes, packed 4-bit codes or dequantised float32."""
+    wtype = _wtype(w)
+    cout, cin, kh, kw = _shape4(w)
+    if out is None:
+        out = _new_output(w.shape, output, w.device)
+    if scales is None:
+        scales = torch.empty(cout, dtype=torch.float32, device=w.device)
+    _check(lib().squant_quantize_ex(w.data_ptr(), wtype, cout, cin, kh, kw, bits, mode, output,
+                                    out.data_ptr(), scales.data_ptr(), _stream_ptr(stream)))
+    return out, scales
+
+
 class BatchPlan:
     """Descriptor array + workspace + outputs of a batched call, built once and reusable."""
 
-    def __init__(self, weights: Sequence[torch.Tensor]):
+    def __init__(self, weights: Sequence[torch.Tensor], output: int = OUT_INT8):
         self.weights = list(weights)
+        self.output = output
+        self.wtype = _wtype(self.weights[0]) if self.weights else W_F32
         n = len(self.weights)
         dev = self.weights[0].device if n else torch.device("cuda")
         self.codes: List[torch.Tensor] = []
         self.scales: List[torch.Tensor] = []
         self.desc = (squant_tensor_t * max(n, 1))()
         for i, w in enumerate(self.weights):
-            _check_weight(w)
+            if _wtype(w) != self.wtype:
+                raise ValueError("all weights of a batch must share one dtype")
             cout, cin, kh, kw = _shape4(w)
-            c = torch.empty(w.shape, dtype=torch.int8, device=dev)
+            c = _new_output(w.shape, output, dev)
             s = torch.empty(cout, dtype=torch.float32, device=dev)
             self.codes.append(c)
             self.scales.append(s)
@@ -156,14 +211,26 @@ class BatchPlan:
         self.workspace = torch.empty(max(self.ws_bytes, 16), dtype=torch.uint8, device=dev)
 
     def run(self, bits: int, mode: int = MODE_EKC, stream=None):
-        _check(lib().squant_quantize_batched(self.desc, self.n, bits, mode,
-                                             self.workspace.data_ptr(), self.ws_bytes,
-                                             _stream_ptr(stream)))
+        _check(lib().squant_quantize_batched_ex(self.desc, self.n, self.wtype, bits, mode,
+                                                self.output, self.workspace.data_ptr(),
+                                                self.ws_bytes, _stream_ptr(stream)))
         return self.codes, self.scales
 
 
 def squant_quantize_batched(weights: Iterable[torch.Tensor], bits: int, mode: int = MODE_EKC,
                             stream=None):
-    """Quantize a set of weight tensors in one call; returns (list of codes, list of scales)."""
-    plan = BatchPlan(list(weights))
+    """Quantize a set of float32 weight tensors in one call; returns (list of codes, list of scales)."""
+    ws = list(weights)
+    for w in ws:
+        _check_weight(w)
+    plan = BatchPlan(ws)
+    _check(lib().squant_quantize_batched(plan.desc, plan.n, bits, mode, plan.workspace.data_ptr(),
+                                         plan.ws_bytes, _stream_ptr(stream)))
+    return plan.codes, plan.scales
+
+
+def squant_quantize_batched_ex(weights: Iterable[torch.Tensor], bits: int, mode: int = MODE_EKC,
+                               output: int = OUT_INT8, stream=None):
+    """The batched call for float32 / float16 / bfloat16 weights and any output format."""
+    plan = BatchPlan(list(weights), output)
     return plan.run(bits, mode, stream)

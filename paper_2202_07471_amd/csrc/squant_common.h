@@ -17,7 +17,7 @@ constexpr int kWave = 64;
 
 struct TensorDesc {
   const float* w;
-  int8_t* codes;
+  void* out;      // codes or dequantised weights, in the launch's output format
   float* scales;
   int32_t M, N, K;
   int32_t first;  // index of this tensor's channel 0 within its launch
@@ -31,6 +31,7 @@ struct LaunchArgs {
   int32_t uniform_m;        // > 0: every tensor of the table has this many channels
   int32_t qmax;
   int32_t mode;
+  int32_t out_format;       // squant_output_t
 };
 
 // ---------------------------------------------------------------------------

@@ -2,6 +2,7 @@
 #pragma once
 
 #include "squant_common.h"
+#include "squant_io.h"
 #include "squant_select.h"
 
 namespace squant {
@@ -241,7 +242,6 @@ __global__ void __launch_bounds__(1024) squant_channel_generic(LaunchArgs a) {
   int8_t* code = reinterpret_cast<int8_t*>(buf + L + (K == 1 ? 0 : 2 * N));  // L codes
 
   const float* wch = d.w + (size_t)m * L;
-  int8_t* out = d.codes + (size_t)m * L;
   const float qmaxf = (float)a.qmax;
 
   // ---- per-channel absmax (Section 4: per-channel quantization range) ----
@@ -253,8 +253,10 @@ __global__ void __launch_bounds__(1024) squant_channel_generic(LaunchArgs a) {
   }
   amax = block_max(amax, red_f);
   if (!(amax > 0.0f)) {  // all-zero channel
-    for (int j = tid; j < L; j += T) out[j] = 0;
+    for (int j = tid; j < L; j += T) code[j] = 0;
     if (tid == 0) d.scales[m] = 1.0f;
+    __syncthreads();
+    emit_channel_bytes(code, L, d.out, m, 1.0f, a.out_format, tid, T);
     return;
   }
   const float s = amax / qmaxf;
@@ -349,16 +351,7 @@ __global__ void __launch_bounds__(1024) squant_channel_generic(LaunchArgs a) {
   }
   __syncthreads();
 
-  // ---- emit int8 codes ----
-  if ((reinterpret_cast<uintptr_t>(out) & 3u) == 0) {
-    const int L4 = L >> 2;
-    const uint32_t* src = reinterpret_cast<const uint32_t*>(code);
-    uint32_t* dst = reinterpret_cast<uint32_t*>(out);
-    for (int j = tid; j < L4; j += T) dst[j] = src[j];
-    for (int j = (L4 << 2) + tid; j < L; j += T) out[j] = code[j];
-  } else {
-    for (int j = tid; j < L; j += T) out[j] = code[j];
-  }
+  emit_channel_bytes(code, L, d.out, m, s, a.out_format, tid, T);
 }
 
 }  // namespace squant

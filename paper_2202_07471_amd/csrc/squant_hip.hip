@@ -69,6 +69,18 @@ int check_common(int32_t bits, int mode) {
   return SQUANT_OK;
 }
 
+// Weight type and output format; `out` may be null when only the enums are checked.
+int check_format(int wtype, int output, int32_t bits, const void* w, const void* out) {
+  if (wtype < SQUANT_W_F32 || wtype > SQUANT_W_BF16) return SQUANT_ERR_FORMAT;
+  if (output < SQUANT_OUT_INT8 || output > SQUANT_OUT_F32) return SQUANT_ERR_FORMAT;
+  if (output == SQUANT_OUT_INT4 && bits > 4) return SQUANT_ERR_BITS;
+  const uintptr_t wmask = wtype == SQUANT_W_F32 ? 3u : 1u;
+  if (reinterpret_cast<uintptr_t>(w) & wmask) return SQUANT_ERR_FORMAT;
+  if (output == SQUANT_OUT_F32 && (reinterpret_cast<uintptr_t>(out) & 3u)) return SQUANT_ERR_FORMAT;
+  if (wtype != SQUANT_W_F32) return SQUANT_ERR_UNSUPPORTED;
+  return SQUANT_OK;
+}
+
 int check_shape(int32_t cout, int32_t cin, int32_t kh, int32_t kw) {
   if (cout <= 0 || cin <= 0 || kh <= 0 || kw <= 0) return SQUANT_ERR_SHAPE;
   const int64_t K = (int64_t)kh * kw;
@@ -134,7 +146,8 @@ Plan plan_tensor(const void* w, const void* codes, int64_t N, int64_t K, int lds
   return Plan{kGeneric, generic_threads(N, K), lds};
 }
 
-int launch_group(const Group& g, const TensorDesc* d_table, int qmax, int mode, hipStream_t st) {
+int launch_group(const Group& g, const TensorDesc* d_table, int qmax, int mode, int output,
+                 hipStream_t st) {
   LaunchArgs a{};
   int64_t total = 0;
   bool uniform = true;
@@ -152,6 +165,7 @@ int launch_group(const Group& g, const TensorDesc* d_table, int qmax, int mode, 
   a.uniform_m = uniform ? g.t[0].M : 0;
   a.qmax = qmax;
   a.mode = mode;
+  a.out_format = output;
   typedef void (*kernel_t)(LaunchArgs);
 #define SQ_K9_ROW(T, KPT)                                                                     \
   {squant_channel_k9<T, SQUANT_MODE_E, KPT>, squant_channel_k9<T, SQUANT_MODE_EK, KPT>,       \
@@ -210,23 +224,43 @@ void timer_release() {
 
 extern "C" {
 
-int squant_quantize(const float* d_w, int32_t cout, int32_t cin, int32_t kh, int32_t kw,
-                    int32_t bits, squant_mode_t mode, int8_t* d_codes, float* d_scales,
-                    void* stream) {
-  if (!d_w || !d_codes || !d_scales) return SQUANT_ERR_NULL;
+int squant_quantize_ex(const void* d_w, squant_wtype_t wtype, int32_t cout, int32_t cin,
+                       int32_t kh, int32_t kw, int32_t bits, squant_mode_t mode,
+                       squant_output_t output, void* d_out, float* d_scales, void* stream) {
+  if (!d_w || !d_out || !d_scales) return SQUANT_ERR_NULL;
   if (int rc = check_shape(cout, cin, kh, kw)) return rc;
   if (int rc = check_common(bits, (int)mode)) return rc;
+  if (int rc = check_format((int)wtype, (int)output, bits, d_w, d_out)) return rc;
   const DeviceLimits lim = device_limits();
   if (!lim.ok) { (void)hipGetLastError(); return SQUANT_ERR_DEVICE; }
   const int64_t K = (int64_t)kh * kw;
-  const Plan p = plan_tensor(d_w, d_codes, cin, K, lim.lds_bytes);
+  const Plan p = plan_tensor(d_w, d_out, cin, K, lim.lds_bytes);
   if (p.lds == 0) return SQUANT_ERR_UNSUPPORTED;
   Group g{p.variant, p.threads, p.lds, {}};
-  g.t.push_back(TensorDesc{d_w, d_codes, d_scales, cout, cin, (int32_t)K, 0});
+  g.t.push_back(TensorDesc{static_cast<const float*>(d_w), d_out, d_scales, cout, cin, (int32_t)K, 0});
   timer_mark(true, (hipStream_t)stream);
-  const int rc = launch_group(g, nullptr, (1 << (bits - 1)) - 1, (int)mode, (hipStream_t)stream);
+  const int rc = launch_group(g, nullptr, (1 << (bits - 1)) - 1, (int)mode, (int)output,
+                              (hipStream_t)stream);
   timer_mark(false, (hipStream_t)stream);
   return rc;
+}
+
+int squant_quantize(const float* d_w, int32_t cout, int32_t cin, int32_t kh, int32_t kw,
+                    int32_t bits, squant_mode_t mode, int8_t* d_codes, float* d_scales,
+                    void* stream) {
+  return squant_quantize_ex(d_w, SQUANT_W_F32, cout, cin, kh, kw, bits, mode, SQUANT_OUT_INT8,
+                            d_codes, d_scales, stream);
+}
+
+size_t squant_output_bytes(int32_t cout, int32_t cin, int32_t kh, int32_t kw, squant_output_t output) {
+  if (check_shape(cout, cin, kh, kw) != SQUANT_OK) return 0;
+  const size_t L = (size_t)cin * kh * kw;
+  switch (output) {
+    case SQUANT_OUT_INT8: return (size_t)cout * L;
+    case SQUANT_OUT_INT4: return (size_t)cout * ((L + 1) / 2);
+    case SQUANT_OUT_F32: return (size_t)cout * L * 4;
+  }
+  return 0;
 }
 
 size_t squant_batched_workspace_bytes(int32_t n_tensors) {
@@ -237,6 +271,14 @@ size_t squant_batched_workspace_bytes(int32_t n_tensors) {
 int squant_quantize_batched(const squant_tensor_t* h_tensors, int32_t n_tensors, int32_t bits,
                             squant_mode_t mode, void* d_workspace, size_t workspace_bytes,
                             void* stream) {
+  return squant_quantize_batched_ex(h_tensors, n_tensors, SQUANT_W_F32, bits, mode,
+                                    SQUANT_OUT_INT8, d_workspace, workspace_bytes, stream);
+}
+
+int squant_quantize_batched_ex(const squant_tensor_t* h_tensors, int32_t n_tensors,
+                               squant_wtype_t wtype, int32_t bits, squant_mode_t mode,
+                               squant_output_t output, void* d_workspace, size_t workspace_bytes,
+                               void* stream) {
   if (n_tensors < 0) return SQUANT_ERR_SHAPE;
   if (n_tensors == 0) return SQUANT_OK;
   if (!h_tensors) return SQUANT_ERR_NULL;
@@ -245,6 +287,7 @@ int squant_quantize_batched(const squant_tensor_t* h_tensors, int32_t n_tensors,
     const squant_tensor_t& t = h_tensors[i];
     if (!t.w || !t.codes || !t.scales) return SQUANT_ERR_NULL;
     if (int rc = check_shape(t.cout, t.cin, t.kh, t.kw)) return rc;
+    if (int rc = check_format((int)wtype, (int)output, bits, t.w, t.codes)) return rc;
   }
   if (!d_workspace || workspace_bytes < squant_batched_workspace_bytes(n_tensors) ||
       (reinterpret_cast<uintptr_t>(d_workspace) & 15u) != 0)
@@ -271,7 +314,8 @@ int squant_quantize_batched(const squant_tensor_t* h_tensors, int32_t n_tensors,
     int64_t first = 0;
     if (!g->t.empty()) first = (int64_t)g->t.back().first + g->t.back().M;
     if (first + t.cout > 0x7fffffff) return SQUANT_ERR_SHAPE;
-    g->t.push_back(TensorDesc{t.w, t.codes, t.scales, t.cout, t.cin, (int32_t)K, (int32_t)first});
+    g->t.push_back(TensorDesc{static_cast<const float*>(t.w), t.codes, t.scales, t.cout, t.cin,
+                              (int32_t)K, (int32_t)first});
   }
 
   hipStream_t st = (hipStream_t)stream;
@@ -292,7 +336,7 @@ int squant_quantize_batched(const squant_tensor_t* h_tensors, int32_t n_tensors,
   timer_mark(true, st);
   size_t offset = 0;
   for (const auto& g : groups) {
-    if (int rc = launch_group(g, table + offset, qmax, (int)mode, st)) return rc;
+    if (int rc = launch_group(g, table + offset, qmax, (int)mode, (int)output, st)) return rc;
     offset += g.t.size();
   }
   timer_mark(false, st);
@@ -354,10 +398,11 @@ const char* squant_status_string(int status) {
     case SQUANT_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case SQUANT_ERR_DEVICE: return "HIP call failed";
     case SQUANT_ERR_UNSUPPORTED: return "output channel too large for one workgroup's LDS";
+    case SQUANT_ERR_FORMAT: return "unknown weight or output type, or misaligned buffer";
     default: return "unknown status";
   }
 }
 
-int squant_version(void) { return 114; }
+int squant_version(void) { return 115; }
 
 }  // extern "C"

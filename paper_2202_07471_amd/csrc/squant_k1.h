@@ -10,7 +10,8 @@
 #pragma once
 
 #include "squant_common.h"
-#include "squant_k9.h"  // vector types and global load / store helpers
+#include "squant_io.h"
+#include "squant_k9.h"  // K9Shared
 #include "squant_select.h"
 
 namespace squant {
@@ -105,13 +106,7 @@ __global__ void __launch_bounds__(MAX_THREADS) squant_channel_k1(LaunchArgs a) {
   }
   __syncthreads();
 
-  int8_t* out = d.codes + (size_t)m * N;
-  if ((nvec & 3) == 0 && (reinterpret_cast<uintptr_t>(out) & 15u) == 0) {
-    const vu4* src4 = reinterpret_cast<const vu4*>(smem);
-    for (int j = tid; j < (nvec >> 2); j += T) store_global_u4(out + 16 * j, src4[j] ^ 0x80808080u);
-  } else {
-    for (int j = tid; j < nvec; j += T) store_global_u1(out + 4 * j, code32[j] ^ 0x80808080u);
-  }
+  emit_channel(code32, nvec, d.out, m, s, a.out_format, tid, T);
 }
 
 }  // namespace squant

@@ -13,63 +13,10 @@
 #pragma once
 
 #include "squant_common.h"
+#include "squant_io.h"
 #include "squant_select.h"
 
 namespace squant {
-
-// tuning switches (compile time)
-#ifndef SQ_OPT_NT_LOAD
-#define SQ_OPT_NT_LOAD 0   // off: the three 12-byte loads of a kernel share cache lines, and
-                           // non-temporal loads were measured 6% slower
-#endif
-#ifndef SQ_OPT_NT_STORE
-#define SQ_OPT_NT_STORE 1  // codes are written once: non-temporal stores (measured 1% faster)
-#endif
-
-typedef float vf3 __attribute__((ext_vector_type(3)));
-typedef float vf4 __attribute__((ext_vector_type(4)));
-typedef uint32_t vu4 __attribute__((ext_vector_type(4)));
-
-// 16-byte load / store through the global (not flat) address space
-__device__ __forceinline__ vf4 load_global_f4(const float* p) {
-#if defined(__HIP_DEVICE_COMPILE__)
-  return *reinterpret_cast<const __attribute__((address_space(1))) vf4*>(reinterpret_cast<uintptr_t>(p));
-#else
-  return *reinterpret_cast<const vf4*>(p);
-#endif
-}
-__device__ __forceinline__ vf3 load_global_f3(const float* p) {
-#if defined(__HIP_DEVICE_COMPILE__)
-#if SQ_OPT_NT_LOAD
-  return __builtin_nontemporal_load(
-      reinterpret_cast<const __attribute__((address_space(1))) vf3*>(reinterpret_cast<uintptr_t>(p)));
-#else
-  return *reinterpret_cast<const __attribute__((address_space(1))) vf3*>(reinterpret_cast<uintptr_t>(p));
-#endif
-#else
-  return *reinterpret_cast<const vf3*>(p);
-#endif
-}
-__device__ __forceinline__ void store_global_u4(void* p, vu4 v) {
-#if defined(__HIP_DEVICE_COMPILE__)
-#if SQ_OPT_NT_STORE
-  __builtin_nontemporal_store(
-      v, reinterpret_cast<__attribute__((address_space(1))) vu4*>(reinterpret_cast<uintptr_t>(p)));
-#else
-  *reinterpret_cast<__attribute__((address_space(1))) vu4*>(reinterpret_cast<uintptr_t>(p)) = v;
-#endif
-#else
-  *reinterpret_cast<vu4*>(p) = v;
-#endif
-}
-__device__ __forceinline__ void store_global_u1(void* p, uint32_t v) {
-#if defined(__HIP_DEVICE_COMPILE__)
-  __builtin_nontemporal_store(
-      v, reinterpret_cast<__attribute__((address_space(1))) uint32_t*>(reinterpret_cast<uintptr_t>(p)));
-#else
-  *reinterpret_cast<uint32_t*>(p) = v;
-#endif
-}
 
 struct K9Shared {
   float red_f[16];
@@ -275,14 +222,7 @@ __global__ void __launch_bounds__(MAX_THREADS) squant_channel_k9(LaunchArgs a) {
   }
   __syncthreads();
 
-  int8_t* out = d.codes + (size_t)m * L;
-  if ((nvec & 3) == 0 && (reinterpret_cast<uintptr_t>(out) & 15u) == 0) {
-    const vu4* src4 = reinterpret_cast<const vu4*>(smem);
-    for (int j = tid; j < (nvec >> 2); j += T) store_global_u4(out + 16 * j, src4[j] ^ 0x80808080u);
-  } else {
-    const uint32_t* code32 = reinterpret_cast<const uint32_t*>(smem);
-    for (int j = tid; j < nvec; j += T) store_global_u1(out + 4 * j, code32[j] ^ 0x80808080u);
-  }
+  emit_channel(reinterpret_cast<const uint32_t*>(smem), nvec, d.out, m, s, a.out_format, tid, T);
 }
 
 }  // namespace squant

@@ -36,7 +36,7 @@ def test_header_symbols_are_exported(L):
 
 def test_status_strings(L):
     seen = set()
-    for s in range(0, 8):
+    for s in range(0, 9):
         txt = L.squant_status_string(s).decode()
         assert txt and txt not in seen
         seen.add(txt)
@@ -88,3 +88,34 @@ def test_binding_refuses_host_tensors():
     import paper_2202_07471_amd as sq
     with pytest.raises(ValueError):
         sq.squant_quantize(torch.zeros(4, 4, 3, 3), 4)
+
+
+def test_output_bytes_and_format_checks(L):
+    assert L.squant_output_bytes(4, 3, 3, 3, 0) == 4 * 27
+    assert L.squant_output_bytes(4, 3, 3, 3, 1) == 4 * 14      # odd rows round up
+    assert L.squant_output_bytes(4, 4, 3, 3, 1) == 4 * 18
+    assert L.squant_output_bytes(4, 3, 3, 3, 2) == 4 * 27 * 4
+    assert L.squant_output_bytes(4, 3, 3, 3, 7) == 0
+    assert L.squant_output_bytes(0, 3, 3, 3, 0) == 0
+    p = ctypes.c_void_p(0x1000)
+    q = lambda *a: L.squant_quantize_ex(*a)
+    assert q(None, 0, 4, 4, 3, 3, 4, 2, 0, p, p, None) == 1
+    assert q(p, 0, 4, 4, 3, 3, 4, 2, 1, None, p, None) == 1
+    assert q(p, 0, 4, 0, 3, 3, 4, 2, 1, p, p, None) == 2
+    assert q(p, 0, 4, 4, 3, 3, 9, 2, 0, p, p, None) == 3
+    assert q(p, 0, 4, 4, 3, 3, 5, 2, 1, p, p, None) == 3       # packed 4-bit output needs bits <= 4
+    assert q(p, 0, 4, 4, 3, 3, 8, 2, 1, p, p, None) == 3
+    assert q(p, 0, 4, 4, 3, 3, 4, 5, 0, p, p, None) == 4
+    assert q(p, 3, 4, 4, 3, 3, 4, 2, 0, p, p, None) == 8       # unknown weight type
+    assert q(p, -1, 4, 4, 3, 3, 4, 2, 0, p, p, None) == 8
+    assert q(p, 0, 4, 4, 3, 3, 4, 2, 3, p, p, None) == 8       # unknown output format
+    assert q(ctypes.c_void_p(0x1002), 0, 4, 4, 3, 3, 4, 2, 0, p, p, None) == 8   # float weights off 4 bytes
+    assert q(p, 0, 4, 4, 3, 3, 4, 2, 2, ctypes.c_void_p(0x1002), p, None) == 8  # float output off 4 bytes
+    from paper_2202_07471_amd.binding import squant_tensor_t
+    arr = (squant_tensor_t * 1)()
+    arr[0] = squant_tensor_t(0x1000, 0x2000, 0x3000, 4, 4, 3, 3)
+    ws = ctypes.c_void_p(0x4000)
+    assert L.squant_quantize_batched_ex(arr, 1, 0, 8, 2, 1, ws, 1024, None) == 3
+    assert L.squant_quantize_batched_ex(arr, 1, 5, 4, 2, 0, ws, 1024, None) == 8
+    assert L.squant_quantize_batched_ex(arr, 1, 0, 4, 2, 9, ws, 1024, None) == 8
+    assert L.squant_quantize_batched_ex(arr, 0, 0, 4, 2, 1, None, 0, None) == 0
