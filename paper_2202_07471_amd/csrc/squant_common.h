@@ -16,7 +16,7 @@ constexpr int32_t kHalf = 1 << 22;  // 0.5 in Q23
 constexpr int kWave = 64;
 
 struct TensorDesc {
-  const float* w;
+  const void* w;  // weights, in the launch's weight type
   void* out;      // codes or dequantised weights, in the launch's output format
   float* scales;
   int32_t M, N, K;
@@ -32,6 +32,7 @@ struct LaunchArgs {
   int32_t qmax;
   int32_t mode;
   int32_t out_format;       // squant_output_t
+  int32_t wtype;            // squant_wtype_t
 };
 
 // ---------------------------------------------------------------------------

@@ -241,13 +241,12 @@ __global__ void __launch_bounds__(1024) squant_channel_generic(LaunchArgs a) {
   int32_t* cidx = (K == 1) ? nullptr : buf + L + N;        // N : candidate element index
   int8_t* code = reinterpret_cast<int8_t*>(buf + L + (K == 1 ? 0 : 2 * N));  // L codes
 
-  const float* wch = d.w + (size_t)m * L;
   const float qmaxf = (float)a.qmax;
 
   // ---- per-channel absmax (Section 4: per-channel quantization range) ----
   float amax = 0.0f;
   for (int j = tid; j < L; j += T) {
-    const float v = wch[j];
+    const float v = load_weight(d.w, (size_t)m * L + j, a.wtype);
     reinterpret_cast<float*>(buf)[j] = v;
     amax = fmaxf(amax, fabsf(v));
   }

@@ -77,7 +77,6 @@ int check_format(int wtype, int output, int32_t bits, const void* w, const void*
   const uintptr_t wmask = wtype == SQUANT_W_F32 ? 3u : 1u;
   if (reinterpret_cast<uintptr_t>(w) & wmask) return SQUANT_ERR_FORMAT;
   if (output == SQUANT_OUT_F32 && (reinterpret_cast<uintptr_t>(out) & 3u)) return SQUANT_ERR_FORMAT;
-  if (wtype != SQUANT_W_F32) return SQUANT_ERR_UNSUPPORTED;
   return SQUANT_OK;
 }
 
@@ -147,7 +146,7 @@ Plan plan_tensor(const void* w, const void* codes, int64_t N, int64_t K, int lds
 }
 
 int launch_group(const Group& g, const TensorDesc* d_table, int qmax, int mode, int output,
-                 hipStream_t st) {
+                 int wtype, hipStream_t st) {
   LaunchArgs a{};
   int64_t total = 0;
   bool uniform = true;
@@ -166,6 +165,7 @@ int launch_group(const Group& g, const TensorDesc* d_table, int qmax, int mode, 
   a.qmax = qmax;
   a.mode = mode;
   a.out_format = output;
+  a.wtype = wtype;
   typedef void (*kernel_t)(LaunchArgs);
 #define SQ_K9_ROW(T, KPT)                                                                     \
   {squant_channel_k9<T, SQUANT_MODE_E, KPT>, squant_channel_k9<T, SQUANT_MODE_EK, KPT>,       \
@@ -237,10 +237,10 @@ int squant_quantize_ex(const void* d_w, squant_wtype_t wtype, int32_t cout, int3
   const Plan p = plan_tensor(d_w, d_out, cin, K, lim.lds_bytes);
   if (p.lds == 0) return SQUANT_ERR_UNSUPPORTED;
   Group g{p.variant, p.threads, p.lds, {}};
-  g.t.push_back(TensorDesc{static_cast<const float*>(d_w), d_out, d_scales, cout, cin, (int32_t)K, 0});
+  g.t.push_back(TensorDesc{d_w, d_out, d_scales, cout, cin, (int32_t)K, 0});
   timer_mark(true, (hipStream_t)stream);
   const int rc = launch_group(g, nullptr, (1 << (bits - 1)) - 1, (int)mode, (int)output,
-                              (hipStream_t)stream);
+                              (int)wtype, (hipStream_t)stream);
   timer_mark(false, (hipStream_t)stream);
   return rc;
 }
@@ -314,7 +314,7 @@ int squant_quantize_batched_ex(const squant_tensor_t* h_tensors, int32_t n_tenso
     int64_t first = 0;
     if (!g->t.empty()) first = (int64_t)g->t.back().first + g->t.back().M;
     if (first + t.cout > 0x7fffffff) return SQUANT_ERR_SHAPE;
-    g->t.push_back(TensorDesc{static_cast<const float*>(t.w), t.codes, t.scales, t.cout, t.cin,
+    g->t.push_back(TensorDesc{t.w, t.codes, t.scales, t.cout, t.cin,
                               (int32_t)K, (int32_t)first});
   }
 
@@ -336,7 +336,7 @@ int squant_quantize_batched_ex(const squant_tensor_t* h_tensors, int32_t n_tenso
   timer_mark(true, st);
   size_t offset = 0;
   for (const auto& g : groups) {
-    if (int rc = launch_group(g, table + offset, qmax, (int)mode, (int)output, st)) return rc;
+    if (int rc = launch_group(g, table + offset, qmax, (int)mode, (int)output, (int)wtype, st)) return rc;
     offset += g.t.size();
   }
   timer_mark(false, st);
@@ -403,6 +403,6 @@ const char* squant_status_string(int status) {
   }
 }
 
-int squant_version(void) { return 115; }
+int squant_version(void) { return 116; }
 
 }  // extern "C"

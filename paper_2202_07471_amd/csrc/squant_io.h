@@ -76,6 +76,46 @@ __device__ __forceinline__ void store_global_u16(void* p, uint16_t v) {
 #endif
 }
 
+// ---- binary16 / bfloat16 weights: widened exactly to binary32 on load ----
+__device__ __forceinline__ float widen_f16(uint32_t bits) {  // low 16 bits
+  return (float)__builtin_bit_cast(_Float16, (uint16_t)bits);
+}
+__device__ __forceinline__ float widen_bf16(uint32_t bits) {  // low 16 bits
+  return __uint_as_float(bits << 16);
+}
+// Both halves of a dword, low half first.
+__device__ __forceinline__ void widen_pair(uint32_t d, bool bf16, float& lo, float& hi) {
+  if (bf16) {
+    lo = __uint_as_float(d << 16);
+    hi = __uint_as_float(d & 0xFFFF0000u);
+  } else {
+    lo = widen_f16(d);
+    hi = widen_f16(d >> 16);
+  }
+}
+__device__ __forceinline__ uint32_t load_global_u1(const uint32_t* p) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  return *reinterpret_cast<const __attribute__((address_space(1))) uint32_t*>(reinterpret_cast<uintptr_t>(p));
+#else
+  return *p;
+#endif
+}
+typedef uint32_t vu2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ vu2 load_global_u2_stream(const void* p) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  return __builtin_nontemporal_load(
+      reinterpret_cast<const __attribute__((address_space(1))) vu2*>(reinterpret_cast<uintptr_t>(p)));
+#else
+  return *reinterpret_cast<const vu2*>(p);
+#endif
+}
+// Element i of a weight tensor of the given squant_wtype_t.
+__device__ __forceinline__ float load_weight(const void* w, size_t i, int wtype) {
+  if (wtype == SQUANT_W_F32) return static_cast<const float*>(w)[i];
+  const uint32_t h = static_cast<const uint16_t*>(w)[i];
+  return wtype == SQUANT_W_BF16 ? widen_bf16(h) : widen_f16(h);
+}
+
 // Low nibbles of the four bytes of c, gathered into 16 bits (byte 0 in bits 0-3).  The
 // +128 bias of a code byte does not reach its low nibble, which is the code's 4-bit
 // two's complement.

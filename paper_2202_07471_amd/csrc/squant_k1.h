@@ -38,14 +38,27 @@ __global__ void __launch_bounds__(MAX_THREADS) squant_channel_k1(LaunchArgs a) {
   int m;
   const TensorDesc d = locate(a, blockIdx.x, m);
   const int N = d.N, nvec = N >> 2;  // cin % 4 == 0
-  const float* src = d.w + (size_t)m * N;
   float w[NE];
+  if (a.wtype == SQUANT_W_F32) {
+    const float* src = static_cast<const float*>(d.w) + (size_t)m * N;
 #pragma unroll
-  for (int j = 0; j < NV; ++j) {
-    const int idx = tid + j * T;
-    vf4 v = {0.0f, 0.0f, 0.0f, 0.0f};
-    if (idx < nvec) v = load_global_f4_stream(src + 4 * idx);
-    w[4 * j] = v.x; w[4 * j + 1] = v.y; w[4 * j + 2] = v.z; w[4 * j + 3] = v.w;
+    for (int j = 0; j < NV; ++j) {
+      const int idx = tid + j * T;
+      vf4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+      if (idx < nvec) v = load_global_f4_stream(src + 4 * idx);
+      w[4 * j] = v.x; w[4 * j + 1] = v.y; w[4 * j + 2] = v.z; w[4 * j + 3] = v.w;
+    }
+  } else {  // 16-bit weights: the same four elements per vector, 8 bytes
+    const uint16_t* src = static_cast<const uint16_t*>(d.w) + (size_t)m * N;
+    const bool bf16 = a.wtype == SQUANT_W_BF16;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+      const int idx = tid + j * T;
+      vu2 v = {0u, 0u};
+      if (idx < nvec) v = load_global_u2_stream(src + 4 * idx);
+      widen_pair(v.x, bf16, w[4 * j], w[4 * j + 1]);
+      widen_pair(v.y, bf16, w[4 * j + 2], w[4 * j + 3]);
+    }
   }
   if (kChannelStage) select_reset(sh.sel);  // before the first barrier
 

@@ -108,11 +108,12 @@ __device__ __forceinline__ void k9_solve(const float (&w)[NW], int q, float s, f
 // (nothing is masked then: the largest |p| of either sign, lowest index first).  Such a
 // kernel has k = 0, so its perturbations are those of plain rounding and are recomputed
 // here from the weights in memory.
-__device__ __noinline__ int2 k9_zero_sum_candidate(const float* wk, float s, float qmaxf) {
+__device__ __noinline__ int2 k9_zero_sum_candidate(const void* w, size_t first, int wtype, float s,
+                                                   float qmaxf) {
   int32_t best = 0, bv = 0;
   int bi = 0;
   for (int i = 0; i < 9; ++i) {
-    float x = wk[i] / s;
+    float x = load_weight(w, first + i, wtype) / s;
     x = fminf(fmaxf(x, -qmaxf), qmaxf);
     const float p = rintf(x) - x;
     const int32_t P = __float2int_rn(p * 8388608.0f);
@@ -132,6 +133,30 @@ __device__ __forceinline__ void k9_load_kernel(float (&w)[NW], int q, const floa
     const vf3 v = load_global_f3(base + (lane_off + 3 * j));
     w[9 * q + 3 * j] = v.x; w[9 * q + 3 * j + 1] = v.y; w[9 * q + 3 * j + 2] = v.z;
   }
+}
+
+// The same for 16-bit weights (binary16 or bfloat16).  Kernel n starts at half-word 9n of
+// the channel, which is dword aligned for even n only, so five aligned dwords starting at
+// half-word 9n - (n & 1) are read and shifted down by one half-word for odd n.  chan32 is the
+// channel's first dword (the channel has 9 * cin half-words, cin % 4 == 0, so it is dword
+// aligned and ends with the last kernel's last half-word: no load reaches past it).
+template <int NW>
+__device__ __forceinline__ void k9_load_kernel16(float (&w)[NW], int q, const uint32_t* chan32,
+                                                 uint32_t n, bool bf16) {
+  const uint32_t h0 = 9u * n;
+  const uint32_t sh = (h0 & 1u) << 4;
+  const uint32_t* p = chan32 + (h0 >> 1);
+  uint32_t d[5];
+#pragma unroll
+  for (int j = 0; j < 5; ++j) d[j] = load_global_u1(p + j);
+  uint32_t u[5];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) u[j] = __builtin_amdgcn_alignbit(d[j + 1], d[j], sh);
+  u[4] = d[4] >> sh;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) widen_pair(u[j], bf16, w[9 * q + 2 * j], w[9 * q + 2 * j + 1]);
+  float unused;
+  widen_pair(u[4], bf16, w[9 * q + 8], unused);
 }
 
 template <int KPT, bool FAST, int MODE>
@@ -166,10 +191,18 @@ __global__ void __launch_bounds__(MAX_THREADS) squant_channel_k9(LaunchArgs a) {
   const int L = 9 * N, nvec = L >> 2;  // dwords of codes (cin % 4 == 0)
   const bool active = tid < G;
   const int t = active ? tid : 0;  // idle threads shadow thread 0's loads and write nothing
-  const float* src = d.w + (size_t)m * L;
   float w[9 * KPT];
+  if (a.wtype == SQUANT_W_F32) {
+    const float* src = static_cast<const float*>(d.w) + (size_t)m * L;
 #pragma unroll
-  for (int q = 0; q < KPT; ++q) k9_load_kernel(w, q, src + (size_t)q * (9 * G), 9u * (uint32_t)t);
+    for (int q = 0; q < KPT; ++q) k9_load_kernel(w, q, src + (size_t)q * (9 * G), 9u * (uint32_t)t);
+  } else {
+    const uint32_t* chan32 =
+        reinterpret_cast<const uint32_t*>(static_cast<const uint16_t*>(d.w) + (size_t)m * L);
+    const bool bf16 = a.wtype == SQUANT_W_BF16;
+#pragma unroll
+    for (int q = 0; q < KPT; ++q) k9_load_kernel16(w, q, chan32, (uint32_t)(t + q * G), bf16);
+  }
   if (kChannelStage) select_reset(sh.sel);  // before the first barrier
 
   float amax = 0.0f;
@@ -196,7 +229,7 @@ __global__ void __launch_bounds__(MAX_THREADS) squant_channel_k9(LaunchArgs a) {
 #pragma unroll
       for (int q = 0; q < KPT; ++q)
         if (zero & (1u << q)) {
-          const int2 z = k9_zero_sum_candidate(src + 9 * (t + q * G), s, qmaxf);
+          const int2 z = k9_zero_sum_candidate(d.w, (size_t)m * L + 9 * (t + q * G), a.wtype, s, qmaxf);
           cv[q] = candidate_word(z.x);
           ci[q] = z.y;
         }
