@@ -33,14 +33,27 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def load_traffic(kernel_version: int):
+K9_SOURCES = ("squant_k9.h", "squant_select.h", "squant_io.h", "squant_common.h", "squant_arith.h")
+
+
+def kernel_source_digest() -> str:
+    """SHA-256 over the sources the 3x3 kernel is compiled from."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in K9_SOURCES:
+        with open(os.path.join(ROOT, "paper_2202_07471_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def load_traffic():
     """HBM bytes per launch measured with rocprofv3 --pmc (see profiles/); None when the
-    kernel has changed since the counters were taken."""
+    kernel's sources have changed since the counters were taken."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     try:
         with open(path) as f:
             t = json.load(f)
-        if int(t.get("kernel_version", -1)) == kernel_version:
+        if t.get("kernel_source_sha256") == kernel_source_digest():
             return float(t["bytes_per_launch"])
     except (OSError, ValueError, KeyError):
         pass
@@ -151,7 +164,7 @@ def main() -> int:
     algo_bytes = (in_bytes + out_bytes) * n_params + 4.0 * n_channels
     achieved = algo_bytes / (k_avg_ms * 1e-3) / 1e9
     headline_io = args.output == "int8" and args.wtype == "f32"
-    traffic = (load_traffic(sq.squant_version())
+    traffic = (load_traffic()
                if args.workload == "c5" and args.tensors is None and headline_io else None)
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,

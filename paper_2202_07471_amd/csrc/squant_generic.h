@@ -225,15 +225,19 @@ __device__ int64_t kernel_stage_wave(int32_t* pk, int8_t* ck, int K, int mode, i
 // ---------------------------------------------------------------------------
 constexpr int kWaveKernelMinK = 32;
 
-__global__ void __launch_bounds__(1024) squant_channel_generic(LaunchArgs a) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  __shared__ float red_f[16];
-  __shared__ int64_t red_i[16];
-  __shared__ uint32_t hist[256];
-  __shared__ uint32_t bcast[4];
+struct GenericShared {
+  float red_f[16];
+  int64_t red_i[16];
+  uint32_t hist[256];
+  uint32_t bcast[4];
+};
 
-  int m;
-  const TensorDesc d = locate(a, blockIdx.x, m);
+__device__ __forceinline__ void generic_channel(const LaunchArgs& a, const TensorDesc& d, int m,
+                                                unsigned char* smem, GenericShared& gs) {
+  float* red_f = gs.red_f;
+  int64_t* red_i = gs.red_i;
+  uint32_t* hist = gs.hist;
+  uint32_t* bcast = gs.bcast;
   const int N = d.N, K = d.K, L = N * K;
   const int T = blockDim.x, tid = threadIdx.x;
   int32_t* buf = reinterpret_cast<int32_t*>(smem);         // L : weights, then Q23 perturbations
@@ -351,6 +355,14 @@ __global__ void __launch_bounds__(1024) squant_channel_generic(LaunchArgs a) {
   __syncthreads();
 
   emit_channel_bytes(code, L, d.out, m, s, a.out_format, tid, T);
+}
+
+__global__ void __launch_bounds__(1024) squant_channel_generic(LaunchArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  __shared__ GenericShared gs;
+  int m;
+  const TensorDesc d = locate(a, blockIdx.x, m);
+  generic_channel(a, d, m, smem, gs);
 }
 
 }  // namespace squant

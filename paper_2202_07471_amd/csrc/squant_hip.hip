@@ -22,6 +22,8 @@
 #include "squant_generic.h"
 #include "squant_k9.h"
 #include "squant_k1.h"
+#include "squant_mixed.h"
+#include "squant_plan.h"
 
 namespace {
 
@@ -96,11 +98,7 @@ struct KernelTimer {
 thread_local KernelTimer g_timer;
 void timer_mark(bool start, hipStream_t st);
 
-enum Variant {
-  kGeneric = 0,
-  kK9x1 = 1, kK9x2 = 2, kK9x4 = 3,             // 3x3 kernels per thread: 1, 2, 4
-  kK1x1 = 4, kK1x2 = 5, kK1x4 = 6, kK1x8 = 7  // 1x1 / FC: 16-byte vectors per thread: 1, 2, 4, 8
-};
+constexpr int kMixed = 100;  // Group::variant of a launch of squant_channel_mixed
 
 struct Group {
   int variant;
@@ -114,35 +112,29 @@ struct Plan { int variant; int threads; size_t lds; };
 inline size_t round_up(size_t v, size_t to) { return (v + to - 1) / to * to; }
 
 // Picks the kernel variant and launch shape for one tensor; lds = 0 means it fits none.
-Plan plan_tensor(const void* w, const void* codes, int64_t N, int64_t K, int lds_limit) {
-  const bool aligned = (reinterpret_cast<uintptr_t>(w) & 15u) == 0 &&
-                       (reinterpret_cast<uintptr_t>(codes) & 3u) == 0;
-  if (K == 9 && (N & 3) == 0 && N <= 4096 && aligned) {
-    // kernels per thread: the largest of 4, 2, 1 that keeps the waves fullest
-    int kpt = 4;
-    double best = 0.0;
-    for (int c : {4, 2, 1}) {
-      const size_t th = round_up((size_t)N / c, kWave);
-      if (th > 256 && c != 4) continue;
-      const double fill = (double)(N / c) / (double)th;
-      if (fill > best + 1e-9) { best = fill; kpt = c; }
+Plan plan_tensor(const void* w, const void* out, int64_t N, int64_t K, int lds_limit) {
+  const int variant = choose_variant(N, K, pointers_aligned(w, out));
+  switch (variant) {
+    case kK9x1: case kK9x2: case kK9x4: {
+      const int kpt = variant == kK9x4 ? 4 : variant == kK9x2 ? 2 : 1;
+      // LDS: the channel's int8 codes
+      return Plan{variant, (int)round_up64(N / kpt), round_up((size_t)9 * N, 16)};
     }
-    const int threads = (int)round_up((size_t)N / kpt, kWave);
-    const int variant = kpt == 4 ? kK9x4 : kpt == 2 ? kK9x2 : kK9x1;
-    return Plan{variant, threads, round_up((size_t)9 * N, 16)};  // LDS: the channel's int8 codes
-  }
-  if (K == 1 && (N & 3) == 0 && N <= 32768 && aligned) {
-    // 16-byte vectors per thread: one full wave per channel while that takes at most four
-    // per thread (measured best), then up to 256 threads with four, then eight
-    const int64_t nvec = N / 4;
-    const int nv = nvec <= 64 ? 1 : nvec <= 128 ? 2 : nvec <= 1024 ? 4 : 8;
-    const int threads = (int)round_up(((size_t)N / 4 + nv - 1) / nv, kWave);
-    const int variant = nv == 1 ? kK1x1 : nv == 2 ? kK1x2 : nv == 4 ? kK1x4 : kK1x8;
-    return Plan{variant, threads, round_up((size_t)N, 16)};  // LDS: the channel's int8 codes
+    case kK1x1: case kK1x2: case kK1x4: case kK1x8: {
+      const int nv = variant == kK1x1 ? 1 : variant == kK1x2 ? 2 : variant == kK1x4 ? 4 : 8;
+      return Plan{variant, (int)round_up64((N / 4 + nv - 1) / nv), round_up((size_t)N, 16)};
+    }
+    default: break;
   }
   const size_t lds = generic_lds_bytes(N, K);
   if (lds + kStaticLds > (size_t)lds_limit) return Plan{kGeneric, 0, 0};
   return Plan{kGeneric, generic_threads(N, K), lds};
+}
+
+// Whether a tensor may join a launch of the mixed kernel: its variant is one the mixed kernel
+// carries (all but the eight-vector 1x1 variant) and fits its workgroup size and LDS.
+bool mixable(const Plan& p, size_t lds_cap) {
+  return p.variant != kK1x8 && p.threads <= kMixedMaxThreads && p.lds <= lds_cap;
 }
 
 int launch_group(const Group& g, const TensorDesc* d_table, int qmax, int mode, int output,
@@ -184,7 +176,10 @@ int launch_group(const Group& g, const TensorDesc* d_table, int qmax, int mode, 
   static const kernel_t k1x4[4] = SQ_K1_ROW(256, 4);
   static const kernel_t k1x8[4] = SQ_K1_ROW(1024, 8);
 #undef SQ_K1_ROW
-  const kernel_t kernel = g.variant == kK1x1   ? k1x1[mode]
+  static const kernel_t mixed[4] = {squant_channel_mixed<SQUANT_MODE_E>, squant_channel_mixed<SQUANT_MODE_EK>,
+                                    squant_channel_mixed<SQUANT_MODE_EKC>, squant_channel_mixed<SQUANT_MODE_EC>};
+  const kernel_t kernel = g.variant == kMixed  ? mixed[mode]
+                          : g.variant == kK1x1 ? k1x1[mode]
                           : g.variant == kK1x2 ? k1x2[mode]
                           : g.variant == kK1x4 ? k1x4[mode]
                           : g.variant == kK1x8 ? k1x8[mode]
@@ -295,27 +290,49 @@ int squant_quantize_batched_ex(const squant_tensor_t* h_tensors, int32_t n_tenso
   const DeviceLimits lim = device_limits();
   if (!lim.ok) { (void)hipGetLastError(); return SQUANT_ERR_DEVICE; }
 
-  // group tensors by launch configuration
-  std::vector<Group> groups;
+  // Group tensors by launch configuration.  Tensors whose variant runs in workgroups of at
+  // most kMixedMaxThreads threads share ONE launch of the mixed kernel when they differ in
+  // variant or launch shape (the layers of a network); a uniform set keeps its own kernel.
+  std::vector<Plan> plans((size_t)n_tensors);
+  const size_t lds_cap = (size_t)lim.lds_bytes - kStaticLds - sizeof(K9Shared) - sizeof(GenericShared);
+  int small_kinds = 0;
+  Plan small_first{};
   for (int32_t i = 0; i < n_tensors; ++i) {
     const squant_tensor_t& t = h_tensors[i];
-    const int64_t K = (int64_t)t.kh * t.kw;
-    const Plan p = plan_tensor(t.w, t.codes, t.cin, K, lim.lds_bytes);
+    Plan p = plan_tensor(t.w, t.codes, t.cin, (int64_t)t.kh * t.kw, lim.lds_bytes);
     if (p.lds == 0) return SQUANT_ERR_UNSUPPORTED;
     // LDS size classes: next power of two >= 2 KB keeps the number of launches small
     size_t cls = 2048;
     while (cls < p.lds) cls <<= 1;
-    cls = std::min(cls, (size_t)lim.lds_bytes - kStaticLds - sizeof(K9Shared));
-    cls = std::max(cls, p.lds);
+    p.lds = std::max(std::min(cls, lds_cap), p.lds);
+    plans[(size_t)i] = p;
+    if (mixable(p, lds_cap)) {
+      if (small_kinds == 0) { small_first = p; small_kinds = 1; }
+      else if (p.variant != small_first.variant || p.threads != small_first.threads ||
+               p.lds != small_first.lds) small_kinds = 2;
+    }
+  }
+  const bool use_mixed = small_kinds > 1;
+  std::vector<Group> groups;
+  for (int32_t i = 0; i < n_tensors; ++i) {
+    const squant_tensor_t& t = h_tensors[i];
+    const Plan& p = plans[(size_t)i];
+    const bool in_mixed = use_mixed && mixable(p, lds_cap);
     Group* g = nullptr;
-    for (auto& c : groups)
-      if (c.variant == p.variant && c.threads == p.threads && c.lds == cls) { g = &c; break; }
-    if (!g) { groups.push_back(Group{p.variant, p.threads, cls, {}}); g = &groups.back(); }
+    for (auto& c : groups) {
+      if (in_mixed ? c.variant == kMixed
+                   : (c.variant == p.variant && c.threads == p.threads && c.lds == p.lds)) { g = &c; break; }
+    }
+    if (!g) {
+      groups.push_back(Group{in_mixed ? kMixed : p.variant, p.threads, p.lds, {}});
+      g = &groups.back();
+    }
+    if (in_mixed) { g->threads = std::max(g->threads, p.threads); g->lds = std::max(g->lds, p.lds); }
     int64_t first = 0;
     if (!g->t.empty()) first = (int64_t)g->t.back().first + g->t.back().M;
     if (first + t.cout > 0x7fffffff) return SQUANT_ERR_SHAPE;
-    g->t.push_back(TensorDesc{t.w, t.codes, t.scales, t.cout, t.cin,
-                              (int32_t)K, (int32_t)first});
+    g->t.push_back(TensorDesc{t.w, t.codes, t.scales, t.cout, t.cin, (int32_t)((int64_t)t.kh * t.kw),
+                              (int32_t)first});
   }
 
   hipStream_t st = (hipStream_t)stream;
@@ -403,6 +420,6 @@ const char* squant_status_string(int status) {
   }
 }
 
-int squant_version(void) { return 116; }
+int squant_version(void) { return 117; }
 
 }  // extern "C"

@@ -25,18 +25,15 @@ __device__ __forceinline__ vf4 load_global_f4_stream(const float* p) {
 #endif
 }
 
-template <int MAX_THREADS, int MODE, int NV>
-__global__ void __launch_bounds__(MAX_THREADS) squant_channel_k1(LaunchArgs a) {
-  extern __shared__ __align__(16) unsigned char smem[];  // N bytes of biased codes
-  __shared__ K9Shared sh;
+template <int MODE, int NV>
+__device__ __forceinline__ void k1_channel(const LaunchArgs& a, const TensorDesc& d, int m,
+                                           unsigned char* smem, K9Shared& sh) {
   constexpr bool kChannelStage = MODE == SQUANT_MODE_EKC || MODE == SQUANT_MODE_EC;
   constexpr int NE = 4 * NV;  // elements per thread
   const int T = blockDim.x, tid = threadIdx.x;
   const float qmaxf = (float)a.qmax;
   uint32_t* code32 = reinterpret_cast<uint32_t*>(smem);
 
-  int m;
-  const TensorDesc d = locate(a, blockIdx.x, m);
   const int N = d.N, nvec = N >> 2;  // cin % 4 == 0
   float w[NE];
   if (a.wtype == SQUANT_W_F32) {
@@ -120,6 +117,15 @@ __global__ void __launch_bounds__(MAX_THREADS) squant_channel_k1(LaunchArgs a) {
   __syncthreads();
 
   emit_channel(code32, nvec, d.out, m, s, a.out_format, tid, T);
+}
+
+template <int MAX_THREADS, int MODE, int NV>
+__global__ void __launch_bounds__(MAX_THREADS) squant_channel_k1(LaunchArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];  // N bytes of biased codes
+  __shared__ K9Shared sh;
+  int m;
+  const TensorDesc d = locate(a, blockIdx.x, m);
+  k1_channel<MODE, NV>(a, d, m, smem, sh);
 }
 
 }  // namespace squant

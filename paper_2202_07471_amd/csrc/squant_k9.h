@@ -176,17 +176,14 @@ __device__ __forceinline__ void k9_solve_all(const float (&w)[9 * KPT], float s,
 // One workgroup per output channel.  Thread t owns the KPT 3x3 kernels t, t + G, t + 2G, ...
 // (G = cin / KPT); KPT is 4 for wide layers and 2 or 1 for narrow ones, so that the waves
 // stay full.
-template <int MAX_THREADS, int MODE, int KPT>
-__global__ void __launch_bounds__(MAX_THREADS) squant_channel_k9(LaunchArgs a) {
-  extern __shared__ __align__(16) unsigned char smem[];  // 9*N bytes of codes
-  __shared__ K9Shared sh;
+template <int MODE, int KPT>
+__device__ __forceinline__ void k9_channel(const LaunchArgs& a, const TensorDesc& d, int m,
+                                           unsigned char* smem, K9Shared& sh) {
   constexpr bool kChannelStage = MODE == SQUANT_MODE_EKC || MODE == SQUANT_MODE_EC;
   const int T = blockDim.x, tid = threadIdx.x;
   const float qmaxf = (float)a.qmax;
   uint8_t* code8 = reinterpret_cast<uint8_t*>(smem);  // biased codes: code + 128
 
-  int m;
-  const TensorDesc d = locate(a, blockIdx.x, m);
   const int N = d.N, G = N / KPT;
   const int L = 9 * N, nvec = L >> 2;  // dwords of codes (cin % 4 == 0)
   const bool active = tid < G;
@@ -256,6 +253,15 @@ __global__ void __launch_bounds__(MAX_THREADS) squant_channel_k9(LaunchArgs a) {
   __syncthreads();
 
   emit_channel(reinterpret_cast<const uint32_t*>(smem), nvec, d.out, m, s, a.out_format, tid, T);
+}
+
+template <int MAX_THREADS, int MODE, int KPT>
+__global__ void __launch_bounds__(MAX_THREADS) squant_channel_k9(LaunchArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];  // 9*N bytes of codes
+  __shared__ K9Shared sh;
+  int m;
+  const TensorDesc d = locate(a, blockIdx.x, m);
+  k9_channel<MODE, KPT>(a, d, m, smem, sh);
 }
 
 }  // namespace squant

@@ -1,0 +1,60 @@
+// Which kernel variant a tensor's channels go through.  One function for the host, which
+// sizes the launch from it, and for the mixed kernel, which picks the variant again per
+// workgroup from the tensor's descriptor, so the two cannot disagree.
+#pragma once
+
+#include <stdint.h>
+
+#include "squant_arith.h"  // SQ_HD
+
+namespace squant {
+
+enum Variant {
+  kGeneric = 0,
+  kK9x1 = 1, kK9x2 = 2, kK9x4 = 3,             // 3x3 kernels per thread: 1, 2, 4
+  kK1x1 = 4, kK1x2 = 5, kK1x4 = 6, kK1x8 = 7  // 1x1 / FC: 16-byte vectors per thread: 1, 2, 4, 8
+};
+
+constexpr int kMaxK9Cin = 4096;   // 3x3 variant: cin % 4 == 0 up to here
+constexpr int kMaxK1Cin = 32768;  // 1x1 variant: cin % 4 == 0 up to here
+
+SQ_HD int64_t round_up64(int64_t v) { return (v + 63) / 64 * 64; }
+
+// Kernel family of a tensor: 9 = the 3x3 kernel, 1 = the 1x1 / FC kernel, 0 = generic.
+// aligned: weights on 16 bytes and output on 4 (what the vector loads / stores need)
+SQ_HD int choose_family(int64_t N, int64_t K, bool aligned) {
+  if (K == 9 && (N & 3) == 0 && N <= kMaxK9Cin && aligned) return 9;
+  if (K == 1 && (N & 3) == 0 && N <= kMaxK1Cin && aligned) return 1;
+  return 0;
+}
+
+// The variant a tensor gets in a launch of its own.
+SQ_HD int choose_variant(int64_t N, int64_t K, bool aligned) {
+  const int family = choose_family(N, K, aligned);
+  if (family == 9) {
+    // kernels per thread: the largest of 4, 2, 1 that keeps the waves fullest
+    // (fill = (N / c) / round_up64(N / c), compared by cross-multiplication)
+    int best_c = 4;
+    int64_t best_num = 0, best_den = 1;
+    for (int c = 4; c >= 1; c >>= 1) {
+      const int64_t th = round_up64(N / c);
+      if (th > 256 && c != 4) continue;
+      const int64_t num = N / c;
+      if (num * best_den > best_num * th) { best_num = num; best_den = th; best_c = c; }
+    }
+    return best_c == 4 ? kK9x4 : best_c == 2 ? kK9x2 : kK9x1;
+  }
+  if (family == 1) {
+    // 16-byte vectors per thread: one full wave per channel while that takes at most four
+    // per thread (measured best), then up to 256 threads with four, then eight
+    const int64_t nvec = N / 4;
+    return nvec <= 64 ? kK1x1 : nvec <= 128 ? kK1x2 : nvec <= 1024 ? kK1x4 : kK1x8;
+  }
+  return kGeneric;
+}
+
+SQ_HD bool pointers_aligned(const void* w, const void* out) {
+  return (reinterpret_cast<uintptr_t>(w) & 15u) == 0 && (reinterpret_cast<uintptr_t>(out) & 3u) == 0;
+}
+
+}  // namespace squant

@@ -175,6 +175,20 @@ def test_batched_equals_single_and_other_modes(sq):
             assert torch.equal(c1, c) and torch.equal(s1, sc)
 
 
+def test_mixed_launch_with_every_variant_and_large_members(sq):
+    """One batched call whose tensors cover every kernel variant: the small ones share one
+    mixed launch, the ones that need more than 256 threads per channel keep their own."""
+    shapes = [(6, 64, 3, 3), (5, 96, 3, 3), (4, 512, 3, 3), (3, 1024, 3, 3), (2, 2048, 3, 3),
+              (9, 128, 1, 1), (7, 512, 1, 1), (5, 2048, 1, 1), (3, 8192, 1, 1), (2, 32768, 1, 1),
+              (33, 17, 3, 3), (96, 1, 3, 3), (5, 3, 7, 7), (3, 5000, 1, 1), (4, 6, 11, 11),
+              (17, 63, 1, 1), (6, 64, 3, 3), (1, 1, 1, 1)]
+    ws = [rand_weights(sh, 400 + i, "heavy" if i % 3 == 0 else "normal") for i, sh in enumerate(shapes)]
+    for bits, mode in ((4, 2), (3, 1), (8, 3), (4, 0)):
+        codes, scales = run_batched(sq, ws, bits, mode)
+        for sh, w, c, sc in zip(shapes, ws, codes, scales):
+            assert_same(c, sc, w, bits, mode, what=f"mixed launch {sh} bits={bits} mode={mode}")
+
+
 def test_config5_slice_batched(sq):
     specs = synth.config_specs(5, n_tensors=6)
     ws = [synth.generate(s) for s in specs]
