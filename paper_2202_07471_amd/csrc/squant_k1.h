@@ -5,8 +5,8 @@
 // SQuant-C candidate (Algorithm 3, "under SQuant" with k = 0).  One workgroup per output
 // channel; a thread takes NV 16-byte vectors of the channel, vector j of thread t being
 // vector t + j*T, so every load instruction of a wave reads 1 KB of consecutive weights.
-// SQuant-E runs in registers, the int8 codes go to LDS four to a dword, and SQuant-C is the
-// same LDS radix select as for the 3x3 kernel, over all cin elements of the channel.
+// SQuant-E runs in registers, the int8 codes go to LDS four to a dword, and SQuant-C is an
+// LDS radix select over the signed perturbations of all cin elements of the channel.
 #pragma once
 
 #include "squant_common.h"
@@ -23,6 +23,226 @@ __device__ __forceinline__ vf4 load_global_f4_stream(const float* p) {
 #else
   return *reinterpret_cast<const vf4*>(p);
 #endif
+}
+
+// ---------------------------------------------------------------------------
+// SQuant-C for one-element kernels.  Every element is a candidate and its candidate value is
+// its own rounding perturbation P (Q23, |P| <= 2^22), so the selection works on P directly:
+// the `need` elements with the largest |P| among those with the sign of the channel sum,
+// lowest index first on ties.  A radix select over the signed value:
+//   level 0  257 bins of P >> 15, counted into LDS before the channel sum (and with it the
+//            wanted sign) is known: negative P in bins 0..127, P >= 0 in bins 128..256.  The
+//            scan runs from the outside in over the wanted sign's bins only.
+//   below    u = P (sum > 0) or ~P (sum < 0) orders the wanted side "larger is better";
+//            bits 14..7 and 7..0 of u get a 256-bin pass each while the boundary bin still
+//            holds more keys than the ranking list takes.
+// A thread keeps the elements still undecided as a bit mask.  P = 0 is no candidate but
+// shares bin 128 with small positive P: when the scan ends in that bin the members are
+// counted again exactly.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void k1_count(SelectShared& sh, int32_t P) {
+  atomicAdd(&sh.hist[(P >> 15) + 128], 1u);
+}
+
+// Level 0 scan, by every wave on its own.  Returns the boundary bin in u units
+// (d = u >> 15 of the need-th best key, 0..128), or -1 when the wanted side holds fewer than
+// `need` keys; need_at = keys still wanted inside that bin, count_at = keys in it.
+__device__ __forceinline__ int k1_scan_top(const uint32_t* hist, int sgn, uint32_t need,
+                                           uint32_t& need_at, uint32_t& count_at) {
+  const int lane = threadIdx.x & (kWave - 1);
+  // traversal order: sum > 0 from bin 259 (padding) down to 128, sum < 0 from bin 0 up to 127
+  const bool on = sgn > 0 ? lane <= 32 : lane <= 31;
+  const int quad = sgn > 0 ? 64 - lane : lane;
+  uint4 h = make_uint4(0, 0, 0, 0);
+  if (on) h = reinterpret_cast<const uint4*>(hist)[quad];
+  const uint32_t a0 = sgn > 0 ? h.w : h.x, a1 = sgn > 0 ? h.z : h.y;
+  const uint32_t a2 = sgn > 0 ? h.y : h.z, a3 = sgn > 0 ? h.x : h.w;
+  const uint32_t mine = a0 + a1 + a2 + a3;
+  const uint32_t incl = wave_prefix_sum(mine);
+  const unsigned long long reach = __ballot(incl >= need);
+  if (reach == 0ull) { need_at = 0; count_at = 0; return -1; }
+  const int l = __builtin_ctzll(reach);
+  const uint32_t above = (uint32_t)__builtin_amdgcn_readlane((int)(incl - mine), l);
+  const uint32_t b0 = (uint32_t)__builtin_amdgcn_readlane((int)a0, l);
+  const uint32_t b1 = (uint32_t)__builtin_amdgcn_readlane((int)a1, l);
+  const uint32_t b2 = (uint32_t)__builtin_amdgcn_readlane((int)a2, l);
+  const uint32_t b3 = (uint32_t)__builtin_amdgcn_readlane((int)a3, l);
+  int t = 4 * l;  // position in traversal order
+  if (above + b0 >= need) { need_at = need - above; count_at = b0; }
+  else if (above + b0 + b1 >= need) { need_at = need - above - b0; count_at = b1; t += 1; }
+  else if (above + b0 + b1 + b2 >= need) { need_at = need - above - b0 - b1; count_at = b2; t += 2; }
+  else { need_at = need - above - b0 - b1 - b2; count_at = b3; t += 3; }
+  // bin index = 259 - t (sum > 0) or t (sum < 0); u >> 15 = bin - 128 resp. ~(bin - 128)
+  return (sgn > 0 ? 131 : 127) - t;
+}
+
+// Ranks the `count` (key, index) pairs of the list against each other: larger key first, then
+// lower index; the first `need` flip.  Four lanes share a pair, each comparing it with every
+// fourth group of four list entries (two 16-byte LDS reads per group), and add their counts
+// up inside the quad.  Slots past `count` hold (0, 0xFFFFFFFF), which ranks below every pair.
+// After a barrier that follows the last push.
+__device__ __forceinline__ void k1_rank_list(SelectShared& sh, uint32_t count, uint32_t need, int sgn,
+                                             uint32_t* code32) {
+  const uint32_t sub = threadIdx.x & 3u, groups = (count + 3u) >> 2;
+  const uint4* key4 = reinterpret_cast<const uint4*>(sh.list_key);
+  const uint4* n4 = reinterpret_cast<const uint4*>(sh.list_n);
+  for (uint32_t i = threadIdx.x >> 2; i < count; i += blockDim.x >> 2) {
+    const uint32_t key = sh.list_key[i], n = sh.list_n[i];
+    int rank = 0;
+    for (uint32_t g = sub; g < groups; g += 4) {
+      const uint4 ek = key4[g], en = n4[g];
+      rank += (ek.x > key || (ek.x == key && en.x < n)) ? 1 : 0;
+      rank += (ek.y > key || (ek.y == key && en.y < n)) ? 1 : 0;
+      rank += (ek.z > key || (ek.z == key && en.z < n)) ? 1 : 0;
+      rank += (ek.w > key || (ek.w == key && en.w < n)) ? 1 : 0;
+    }
+    rank += __builtin_amdgcn_update_dpp(0, rank, 0xB1, 0xf, 0xf, true);  // quad_perm [1,0,3,2]
+    rank += __builtin_amdgcn_update_dpp(0, rank, 0x4E, 0xf, 0xf, true);  // quad_perm [2,3,0,1]
+    if (sub == 0 && (uint32_t)rank < need) flip_code(code32, (int)n, sgn);
+  }
+}
+
+// Empties the ranking list (see k1_rank_list); with select_reset, before the first barrier.
+__device__ __forceinline__ void k1_list_reset(SelectShared& sh) {
+  for (int b = threadIdx.x; b < kListCap / 4; b += blockDim.x) {
+    reinterpret_cast<uint4*>(sh.list_key)[b] = make_uint4(0, 0, 0, 0);
+    reinterpret_cast<uint4*>(sh.list_n)[b] = make_uint4(~0u, ~0u, ~0u, ~0u);
+  }
+}
+
+__device__ __forceinline__ void k1_push(SelectShared& sh, uint32_t key, int n) {
+  const uint32_t slot = atomicAdd(&sh.list_count, 1u);
+  sh.list_key[slot] = key;
+  sh.list_n[slot] = (uint32_t)n;
+}
+
+// P[q] is element 4 * (tid + (q / 4) * T) + (q % 4) of the channel; elements past the
+// channel's end hold P = 0.  All threads of the workgroup call this after the barrier that
+// follows the last k1_count.
+template <int NE>
+__device__ __forceinline__ void k1_channel_stage(const int32_t (&P)[NE], int sgn, uint32_t need,
+                                                 uint32_t* code32, SelectShared& sh) {
+  static_assert(NE <= 32, "the live mask is 32 bits");
+  const int T = blockDim.x, tid = threadIdx.x;
+  const int32_t smask = sgn < 0 ? -1 : 0;
+  auto elem = [&](int q) { return 4 * (tid + (q >> 2) * T) + (q & 3); };
+
+  uint32_t count = 0, need_at = 0;
+  const int d = k1_scan_top(sh.hist, sgn, need, need_at, count);
+  if (d < 0) {  // fewer candidates of the wanted sign than flips wanted: all of them flip
+#pragma unroll
+    for (int q = 0; q < NE; ++q)
+      if (sgn > 0 ? P[q] > 0 : P[q] < 0) flip_code(code32, elem(q), sgn);
+    return;
+  }
+  need = need_at;
+  const int32_t thr_member = d << 15, thr_flip = (d + 1) << 15;
+  if (count == need && !(sgn > 0 && d == 0)) {
+    // every member of the boundary bin flips (the bin that P = 0 shares needs its real count)
+#pragma unroll
+    for (int q = 0; q < NE; ++q)
+      if ((P[q] ^ smask) >= thr_member) flip_code(code32, elem(q), sgn);
+    return;
+  }
+  if (count <= (uint32_t)kListCap) {
+    // the usual case: the boundary bin's members go straight to the ranking list
+#pragma unroll
+    for (int q = 0; q < NE; ++q) {
+      const int32_t u = P[q] ^ smask;
+      if (u >= thr_member) {
+        if (u >= thr_flip) flip_code(code32, elem(q), sgn);
+        else if (u > 0 || smask != 0) k1_push(sh, (uint32_t)u, elem(q));  // P = 0 is no candidate
+      }
+    }
+    __syncthreads();
+    count = sh.list_count;  // exact: without the P = 0 elements that bin 128 also counts
+    k1_rank_list(sh, count, need < count ? need : count, sgn, code32);
+    return;
+  }
+  uint32_t live = 0;
+#pragma unroll
+  for (int q = 0; q < NE; ++q) {
+    const int32_t u = P[q] ^ smask;
+    if (u >= thr_member) {
+      if (u >= thr_flip) flip_code(code32, elem(q), sgn);
+      else if (u > 0 || smask != 0) live |= 1u << q;  // P = 0 is no candidate
+    }
+  }
+  if (sgn > 0 && d == 0) {  // the bin that P = 0 shares: count its real members
+    __syncthreads();
+    if (tid == 0) sh.wave_cnt[16] = 0;
+    __syncthreads();
+    if (live) atomicAdd(&sh.wave_cnt[16], (uint32_t)__popc(live));
+    __syncthreads();
+    count = sh.wave_cnt[16];
+    if (count < need) need = count;
+    if (count == 0) return;
+  }
+
+  // ---- a crowded bin: histogram passes over bits 14..7, then 7..0 of u ----
+  int shift = 15;
+  while (count > (uint32_t)kListCap && count != need && shift > 0) {
+    shift = shift == 15 ? 7 : 0;
+    __syncthreads();  // every wave has finished reading the histogram
+    for (int b = tid; b < 256; b += T) sh.hist[b] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < NE; ++q)
+      if (live & (1u << q)) atomicAdd(&sh.hist[((uint32_t)(P[q] ^ smask) >> shift) & 255u], 1u);
+    __syncthreads();
+    const uint32_t d2 = scan_histogram_top(sh.hist, need, need_at, count);
+    need = need_at;
+#pragma unroll
+    for (int q = 0; q < NE; ++q) {
+      if (!(live & (1u << q))) continue;
+      const uint32_t dq = ((uint32_t)(P[q] ^ smask) >> shift) & 255u;
+      if (dq > d2) flip_code(code32, elem(q), sgn);
+      if (dq != d2) live &= ~(1u << q);
+    }
+  }
+
+  // `count` elements are still live (equal down to bit `shift`); `need` of them flip
+  if (count == need) {
+#pragma unroll
+    for (int q = 0; q < NE; ++q)
+      if (live & (1u << q)) flip_code(code32, elem(q), sgn);
+    return;
+  }
+  if (count <= (uint32_t)kListCap) {
+#pragma unroll
+    for (int q = 0; q < NE; ++q)
+      if (live & (1u << q)) k1_push(sh, (uint32_t)(P[q] ^ smask), elem(q));
+    __syncthreads();
+    k1_rank_list(sh, count, need, sgn, code32);
+    return;
+  }
+  // more than kListCap elements equal in all their bits: the lowest indices flip.  The four
+  // elements of a vector are consecutive and vectors ascend with the thread, so inside round
+  // j an exclusive prefix count over the threads ranks them; the rounds follow each other.
+  const int lane = tid & (kWave - 1), wid = tid / kWave;
+  const int nw = (T + kWave - 1) / kWave;
+  uint32_t done = 0;
+  for (int round = 0; round < NE / 4; ++round) {
+    const uint32_t bits = (live >> (4 * round)) & 15u;
+    const uint32_t mine = (uint32_t)__popc(bits);
+    const uint32_t incl = wave_prefix_sum(mine);
+    __syncthreads();
+    if (lane == kWave - 1) sh.wave_cnt[wid] = incl;
+    __syncthreads();
+    uint32_t base = done + incl - mine, total = 0;
+    for (int w = 0; w < nw; ++w) {
+      const uint32_t c = sh.wave_cnt[w];
+      if (w < wid) base += c;
+      total += c;
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (bits & (1u << e)) {
+        if (base < need) flip_code(code32, elem(4 * round + e), sgn);
+        ++base;
+      }
+    done += total;
+  }
 }
 
 template <int MODE, int NV>
@@ -57,7 +277,7 @@ __device__ __forceinline__ void k1_channel(const LaunchArgs& a, const TensorDesc
       widen_pair(v.y, bf16, w[4 * j + 2], w[4 * j + 3]);
     }
   }
-  if (kChannelStage) select_reset(sh.sel);  // before the first barrier
+  if (kChannelStage) { select_reset(sh.sel); k1_list_reset(sh.sel); }  // before the first barrier
 
   float amax = 0.0f;
 #pragma unroll
@@ -70,7 +290,7 @@ __device__ __forceinline__ void k1_channel(const LaunchArgs& a, const TensorDesc
 
   // ---- SQuant-E (Algorithm 1): code, and the element's perturbation as candidate word ----
   int32_t esum = 0;
-  uint32_t cw[NE];
+  int32_t P[NE];
 #pragma unroll
   for (int j = 0; j < NV; ++j) {
     uint32_t packed = 0;
@@ -83,9 +303,8 @@ __device__ __forceinline__ void k1_channel(const LaunchArgs& a, const TensorDesc
       packed = __builtin_amdgcn_cvt_pk_u8_f32(c + 128.0f, e, packed);
       if (kChannelStage) {
         const float p = c - xc;  // exact
-        const int32_t P = __float_as_int(__builtin_fmaf(p, 8388608.0f, 12582912.0f)) - 0x4B400000;
-        esum += P;
-        cw[4 * j + e] = candidate_word(P);
+        P[4 * j + e] = __float_as_int(__builtin_fmaf(p, 8388608.0f, 12582912.0f)) - 0x4B400000;
+        esum += P[4 * j + e];
       }
     }
     const int idx = tid + j * T;
@@ -93,26 +312,13 @@ __device__ __forceinline__ void k1_channel(const LaunchArgs& a, const TensorDesc
   }
 
   if (kChannelStage) {
+    // elements past the channel's end were loaded as 0, so their P is 0: no candidate
 #pragma unroll
-    for (int j = 0; j < NV; ++j)
-      if (tid + j * T < nvec) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) count_candidate(sh.sel, cw[4 * j + e]);
-      }
+    for (int q = 0; q < NE; ++q) k1_count(sh.sel, P[q]);
     const int64_t ec = block_sum_dpp1(esum, sh.red_i);  // its barrier publishes codes and histogram
     const int sgn = sign_of(ec);
     const int64_t kc = flips_for(ec < 0 ? -ec : ec);
-    if (kc > 0) {
-      int pos[NE];
-#pragma unroll
-      for (int j = 0; j < NV; ++j)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          pos[4 * j + e] = 4 * (tid + j * T) + e;
-          if (tid + j * T >= nvec) cw[4 * j + e] = kNoCandidate;
-        }
-      channel_stage<NE, 4>(cw, pos, pos, sgn, (uint32_t)(kc > N ? N : kc), code32, sh.sel);
-    }
+    if (kc > 0) k1_channel_stage<NE>(P, sgn, (uint32_t)(kc > N ? N : kc), code32, sh.sel);
   }
   __syncthreads();
 

@@ -18,7 +18,7 @@
 
 namespace squant {
 
-struct K9Shared {
+struct alignas(16) K9Shared {
   float red_f[16];
   int64_t red_i[16];
   SelectShared sel;

@@ -46,7 +46,9 @@ SQ_HD int choose_variant(int64_t N, int64_t K, bool aligned) {
   }
   if (family == 1) {
     // 16-byte vectors per thread: one full wave per channel while that takes at most four
-    // per thread (measured best), then up to 256 threads with four, then eight
+    // per thread, then up to 256 threads with four, then eight (measured: spreading a
+    // channel over more threads sooner is up to 1.6x slower, the workgroup-wide steps of
+    // the channel stage then run in more waves)
     const int64_t nvec = N / 4;
     return nvec <= 64 ? kK1x1 : nvec <= 128 ? kK1x2 : nvec <= 1024 ? kK1x4 : kK1x8;
   }

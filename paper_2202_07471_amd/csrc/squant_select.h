@@ -29,9 +29,10 @@ constexpr int kListRank = SQ_TUNE_LIST_RANK;  // rank through the list up to thi
 constexpr int kHistDummy = 512;  // bin of "no candidate"
 constexpr uint32_t kNoDigit = 0xFFFFFFFFu;
 
-struct SelectShared {
+struct alignas(16) SelectShared {
   uint32_t hist[528];  // [0,256): v > 0, [256,512): v < 0, 512: none; 528 = 132 x 16 bytes
   uint32_t list_count;
+  uint32_t pad_[3];  // keeps the lists on 16 bytes
   uint32_t list_key[kListCap];
   uint32_t list_n[kListCap];
   uint32_t wave_cnt[17];
