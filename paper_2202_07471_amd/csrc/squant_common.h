@@ -47,13 +47,20 @@ __device__ __forceinline__ TensorDesc locate(const LaunchArgs& a, int g, int& m)
   int t;
   if (a.uniform_m > 0) {
     t = g / a.uniform_m;
-  } else {  // last t with first[t] <= g
-    int lo = 0, hi = a.n_tensors - 1;
-    while (lo < hi) {
-      const int mid = (lo + hi + 1) >> 1;
-      if (a.table[mid].first <= g) lo = mid; else hi = mid - 1;
+  } else {
+    // last t with first[t] <= g.  The offsets ascend, so t + 1 is the number of tensors whose
+    // first channel is <= g: every lane fetches one offset (64 per step, one memory latency
+    // instead of the chain of dependent loads of a binary search) and a ballot counts them.
+    const int lane = threadIdx.x & (kWave - 1);
+    int below = 0;
+    for (int base = 0; base < a.n_tensors; base += kWave) {
+      const int i = base + lane;
+      const int first = i < a.n_tensors ? a.table[i].first : 0x7fffffff;
+      const int cnt = __popcll(__ballot(first <= g));
+      below += cnt;
+      if (cnt < kWave) break;
     }
-    t = lo;
+    t = __builtin_amdgcn_readfirstlane(below - 1);
   }
   const TensorDesc d = a.table[t];
   m = g - d.first;

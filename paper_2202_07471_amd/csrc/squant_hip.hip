@@ -98,7 +98,8 @@ struct KernelTimer {
 thread_local KernelTimer g_timer;
 void timer_mark(bool start, hipStream_t st);
 
-constexpr int kMixed = 100;  // Group::variant of a launch of squant_channel_mixed
+constexpr int kMixed = 100;      // Group::variant of a launch of squant_channel_mixed
+constexpr int kMixedWave = 101;  // the same for the tensors whose channels take one wave each
 
 struct Group {
   int variant;
@@ -178,7 +179,7 @@ int launch_group(const Group& g, const TensorDesc* d_table, int qmax, int mode, 
 #undef SQ_K1_ROW
   static const kernel_t mixed[4] = {squant_channel_mixed<SQUANT_MODE_E>, squant_channel_mixed<SQUANT_MODE_EK>,
                                     squant_channel_mixed<SQUANT_MODE_EKC>, squant_channel_mixed<SQUANT_MODE_EC>};
-  const kernel_t kernel = g.variant == kMixed  ? mixed[mode]
+  const kernel_t kernel = (g.variant == kMixed || g.variant == kMixedWave) ? mixed[mode]
                           : g.variant == kK1x1 ? k1x1[mode]
                           : g.variant == kK1x2 ? k1x2[mode]
                           : g.variant == kK1x4 ? k1x4[mode]
@@ -318,13 +319,16 @@ int squant_quantize_batched_ex(const squant_tensor_t* h_tensors, int32_t n_tenso
     const squant_tensor_t& t = h_tensors[i];
     const Plan& p = plans[(size_t)i];
     const bool in_mixed = use_mixed && mixable(p, lds_cap);
+    // two mixed launches at most: one-wave channels keep one-wave workgroups (four times as
+    // many of them fit a compute unit), the rest share a launch of wider workgroups
+    const int mixed_kind = p.threads <= kWave ? kMixedWave : kMixed;
     Group* g = nullptr;
     for (auto& c : groups) {
-      if (in_mixed ? c.variant == kMixed
+      if (in_mixed ? c.variant == mixed_kind
                    : (c.variant == p.variant && c.threads == p.threads && c.lds == p.lds)) { g = &c; break; }
     }
     if (!g) {
-      groups.push_back(Group{in_mixed ? kMixed : p.variant, p.threads, p.lds, {}});
+      groups.push_back(Group{in_mixed ? mixed_kind : p.variant, p.threads, p.lds, {}});
       g = &groups.back();
     }
     if (in_mixed) { g->threads = std::max(g->threads, p.threads); g->lds = std::max(g->lds, p.lds); }
