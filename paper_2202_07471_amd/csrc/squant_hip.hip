@@ -424,6 +424,6 @@ const char* squant_status_string(int status) {
   }
 }
 
-int squant_version(void) { return 117; }
+int squant_version(void) { return 118; }
 
 }  // extern "C"
