@@ -75,9 +75,9 @@ def main() -> int:
                     help="cout,cin,kh,kw: replace the workload by --count He-normal tensors of this shape "
                          "(exploration only; not the headline configuration)")
     ap.add_argument("--count", type=int, default=1)
-    ap.add_argument("--output", default="int8", choices=["int8", "int4", "f32"],
+    ap.add_argument("--output", default="int8", choices=["int8", "int4", "f32", "bf16"],
                     help="what the solver writes per weight: int8 codes (headline), packed 4-bit "
-                         "codes, or dequantised float32")
+                         "codes, or dequantised float32 / bfloat16")
     ap.add_argument("--wtype", default="f32", choices=["f32", "f16", "bf16"],
                     help="element type the weights are handed over in (headline: f32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -160,7 +160,7 @@ def main() -> int:
     k_avg_ms = float(np.mean(kernel_ms))
     # bytes read + written per weight (4 + 1 in the headline configuration), 4 B per scale
     in_bytes = {"f32": 4.0, "f16": 2.0, "bf16": 2.0}[args.wtype]
-    out_bytes = {"int8": 1.0, "int4": 0.5, "f32": 4.0}[args.output]
+    out_bytes = {"int8": 1.0, "int4": 0.5, "f32": 4.0, "bf16": 2.0}[args.output]
     algo_bytes = (in_bytes + out_bytes) * n_params + 4.0 * n_channels
     achieved = algo_bytes / (k_avg_ms * 1e-3) / 1e9
     headline_io = args.output == "int8" and args.wtype == "f32"
@@ -202,6 +202,9 @@ def main() -> int:
                 rc = oracle.pack_int4(rc)
             elif args.output == "f32":
                 rc, gc = oracle.dequantize(rc, rs).view(np.uint32), gc.view(np.uint32)
+            elif args.output == "bf16":
+                rc = oracle.dequantize_bf16(rc, rs)
+                gc = plan.codes[i].view(torch.int16).cpu().numpy().view(np.uint16)
             mism += int((gc != rc).sum()) + int((gs.view(np.uint32) != rs.view(np.uint32)).sum())
         cpu_baseline = {"value": round(sample_params / cpu_s / 1e9, 5), "unit": "Gparams/s",
                         "cores": threads, "kind": "oracle",

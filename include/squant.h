@@ -76,11 +76,14 @@ typedef enum {
  *         element 2j+1 in its high nibble, each the code's 4-bit two's complement; the
  *         unused high nibble of an odd row's last byte is 0.
  *   F32   the dequantised weight (float)code * scales[m] (one binary32 multiply), the
- *         tensor's own layout. */
+ *         tensor's own layout.
+ *   BF16  that binary32 product rounded to bfloat16 (round to nearest, ties to even),
+ *         2 bytes per weight, the tensor's own layout. */
 typedef enum {
   SQUANT_OUT_INT8 = 0,
   SQUANT_OUT_INT4 = 1,
-  SQUANT_OUT_F32 = 2
+  SQUANT_OUT_F32 = 2,
+  SQUANT_OUT_BF16 = 3
 } squant_output_t;
 
 /* Element type of the weights handed in.  The solver's arithmetic is binary32 whatever the
@@ -125,7 +128,7 @@ size_t squant_output_bytes(int32_t cout, int32_t cin, int32_t kh, int32_t kw, sq
 /* squant_quantize / squant_quantize_batched with the weight type and the output format
  * chosen by the caller (Algorithm 1; Section 2.2 for the dequantised form).  d_w holds
  * cout*cin*kh*kw elements of `wtype`, aligned to their size; d_out is a buffer of
- * squant_output_bytes() bytes, aligned to 4 bytes for F32 output; in the batched call the
+ * squant_output_bytes() bytes, aligned to 4 bytes for F32 and to 2 for BF16 output; in the batched call the
  * `w` and `codes` members of each descriptor play these two roles and every tensor shares
  * wtype and output.  SQUANT_OUT_INT4 needs bits <= 4 (SQUANT_ERR_BITS otherwise).  With
  * SQUANT_W_F32 and SQUANT_OUT_INT8 the calls are the plain ones above. */

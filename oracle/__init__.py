@@ -45,6 +45,8 @@ def lib():
         i64 = ctypes.c_int64
         L.squant_oracle_pack_int4.argtypes = [vp, i64, i64, vp]
         L.squant_oracle_dequantize.argtypes = [vp, vp, i64, i64, vp]
+        L.squant_oracle_dequantize_bf16.argtypes = [vp, vp, i64, i64, vp]
+        L.squant_oracle_dequantize_bf16.restype = ctypes.c_int
         L.squant_oracle_widen_f16.argtypes = [vp, i64, vp]
         L.squant_oracle_widen_bf16.argtypes = [vp, i64, vp]
         for f in (L.squant_oracle_pack_int4, L.squant_oracle_dequantize,
@@ -135,6 +137,19 @@ def dequantize(codes, scales):
                                         out.ctypes.data)
     if rc != 0:
         raise ValueError(f"squant_oracle_dequantize failed with status {rc}")
+    return out
+
+
+def dequantize_bf16(codes, scales):
+    """code * scale rounded to bfloat16, as uint16 bit patterns, same shape as codes."""
+    c = np.ascontiguousarray(codes, dtype=np.int8)
+    s = np.ascontiguousarray(scales, dtype=np.float32)
+    cout = c.shape[0]
+    out = np.empty(c.shape, dtype=np.uint16)
+    rc = lib().squant_oracle_dequantize_bf16(c.ctypes.data, s.ctypes.data, cout, c.size // cout,
+                                             out.ctypes.data)
+    if rc != 0:
+        raise ValueError(f"squant_oracle_dequantize_bf16 failed with status {rc}")
     return out
 
 

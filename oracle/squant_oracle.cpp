@@ -51,6 +51,7 @@
 #include <cmath>
 #include <cstdint>
 #include <cstdlib>
+#include <cstring>
 #include <thread>
 #include <vector>
 
@@ -296,6 +297,27 @@ int squant_oracle_dequantize(const int8_t* codes, const float* scales, int64_t c
   if (cout <= 0 || len <= 0) return 2;
   for (int64_t m = 0; m < cout; ++m)
     for (int64_t i = 0; i < len; ++i) out[m * len + i] = (float)codes[m * len + i] * scales[m];
+  return 0;
+}
+
+// The same product rounded to bfloat16 (the upper 16 bits of a binary32), round to nearest,
+// ties to even: the two candidates are the binary32 value with its low 16 bits cleared and
+// that plus one unit of the bfloat16 last place; the nearer one wins, an exact tie goes to
+// the one whose last kept bit is 0.  Finite values only.
+int squant_oracle_dequantize_bf16(const int8_t* codes, const float* scales, int64_t cout,
+                                  int64_t len, uint16_t* out) {
+  if (!codes || !scales || !out) return 1;
+  if (cout <= 0 || len <= 0) return 2;
+  for (int64_t m = 0; m < cout; ++m)
+    for (int64_t i = 0; i < len; ++i) {
+      const float v = (float)codes[m * len + i] * scales[m];
+      uint32_t bits;
+      std::memcpy(&bits, &v, 4);
+      const uint32_t low = bits & 0xFFFFu;   // what is cut off
+      uint32_t kept = bits >> 16;            // sign, exponent, 7 fraction bits
+      if (low > 0x8000u || (low == 0x8000u && (kept & 1u))) kept += 1;  // magnitude grows either sign
+      out[m * len + i] = (uint16_t)kept;
+    }
   return 0;
 }
 

@@ -16,8 +16,8 @@ LIB_PATH = os.path.join(_HERE, "libsquant_hip.so")
 
 MODE_E, MODE_EK, MODE_EKC, MODE_EC = 0, 1, 2, 3
 MODES = {"E": MODE_E, "EK": MODE_EK, "EKC": MODE_EKC, "EC": MODE_EC}
-OUT_INT8, OUT_INT4, OUT_F32 = 0, 1, 2
-OUTPUTS = {"int8": OUT_INT8, "int4": OUT_INT4, "f32": OUT_F32}
+OUT_INT8, OUT_INT4, OUT_F32, OUT_BF16 = 0, 1, 2, 3
+OUTPUTS = {"int8": OUT_INT8, "int4": OUT_INT4, "f32": OUT_F32, "bf16": OUT_BF16}
 W_F32, W_F16, W_BF16 = 0, 1, 2
 _WTYPES = {torch.float32: W_F32, torch.float16: W_F16, torch.bfloat16: W_BF16}
 
@@ -140,12 +140,14 @@ def _wtype(w: torch.Tensor) -> int:
 
 
 def _new_output(shape, output: int, device) -> torch.Tensor:
-    """An output buffer of the format's shape: int8 / float32 like the weights, or uint8
+    """An output buffer of the format's shape: int8 / float32 / bfloat16 like the weights, or uint8
     [cout, (cin*kh*kw + 1) // 2] for packed 4-bit codes."""
     if output == OUT_INT8:
         return torch.empty(shape, dtype=torch.int8, device=device)
     if output == OUT_F32:
         return torch.empty(shape, dtype=torch.float32, device=device)
+    if output == OUT_BF16:
+        return torch.empty(shape, dtype=torch.bfloat16, device=device)
     if output == OUT_INT4:
         n = 1
         for d in shape[1:]:

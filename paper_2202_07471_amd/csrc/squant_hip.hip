@@ -74,11 +74,12 @@ int check_common(int32_t bits, int mode) {
 // Weight type and output format; `out` may be null when only the enums are checked.
 int check_format(int wtype, int output, int32_t bits, const void* w, const void* out) {
   if (wtype < SQUANT_W_F32 || wtype > SQUANT_W_BF16) return SQUANT_ERR_FORMAT;
-  if (output < SQUANT_OUT_INT8 || output > SQUANT_OUT_F32) return SQUANT_ERR_FORMAT;
+  if (output < SQUANT_OUT_INT8 || output > SQUANT_OUT_BF16) return SQUANT_ERR_FORMAT;
   if (output == SQUANT_OUT_INT4 && bits > 4) return SQUANT_ERR_BITS;
   const uintptr_t wmask = wtype == SQUANT_W_F32 ? 3u : 1u;
   if (reinterpret_cast<uintptr_t>(w) & wmask) return SQUANT_ERR_FORMAT;
   if (output == SQUANT_OUT_F32 && (reinterpret_cast<uintptr_t>(out) & 3u)) return SQUANT_ERR_FORMAT;
+  if (output == SQUANT_OUT_BF16 && (reinterpret_cast<uintptr_t>(out) & 1u)) return SQUANT_ERR_FORMAT;
   return SQUANT_OK;
 }
 
@@ -255,6 +256,7 @@ size_t squant_output_bytes(int32_t cout, int32_t cin, int32_t kh, int32_t kw, sq
     case SQUANT_OUT_INT8: return (size_t)cout * L;
     case SQUANT_OUT_INT4: return (size_t)cout * ((L + 1) / 2);
     case SQUANT_OUT_F32: return (size_t)cout * L * 4;
+    case SQUANT_OUT_BF16: return (size_t)cout * L * 2;
   }
   return 0;
 }
@@ -424,6 +426,6 @@ const char* squant_status_string(int status) {
   }
 }
 
-int squant_version(void) { return 118; }
+int squant_version(void) { return 119; }
 
 }  // extern "C"

@@ -18,6 +18,7 @@ namespace squant {
 typedef float vf3 __attribute__((ext_vector_type(3)));
 typedef float vf4 __attribute__((ext_vector_type(4)));
 typedef uint32_t vu4 __attribute__((ext_vector_type(4)));
+typedef uint32_t vu2 __attribute__((ext_vector_type(2)));
 
 // 16-byte load / store through the global (not flat) address space
 __device__ __forceinline__ vf4 load_global_f4(const float* p) {
@@ -100,7 +101,6 @@ __device__ __forceinline__ uint32_t load_global_u1(const uint32_t* p) {
   return *p;
 #endif
 }
-typedef uint32_t vu2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ vu2 load_global_u2_stream(const void* p) {
 #if defined(__HIP_DEVICE_COMPILE__)
   return __builtin_nontemporal_load(
@@ -139,6 +139,20 @@ __device__ __forceinline__ vf4 dequant4(uint32_t c, float s) {
   return v;
 }
 
+// binary32 to bfloat16 bits, round to nearest, ties to even (finite inputs).
+__device__ __forceinline__ uint32_t bf16_bits(float v) {
+  const uint32_t b = __float_as_uint(v);
+  return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ void store_global_u2(void* p, vu2 v) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  __builtin_nontemporal_store(
+      v, reinterpret_cast<__attribute__((address_space(1))) vu2*>(reinterpret_cast<uintptr_t>(p)));
+#else
+  *reinterpret_cast<vu2*>(p) = v;
+#endif
+}
+
 // Writes output channel m of a tensor from its biased codes in LDS (nvec dwords, so the
 // channel has 4 * nvec elements) in the requested format (squant_output_t).  Called by the
 // whole workgroup after a barrier; 16-byte stores where the channel's row is aligned.
@@ -167,6 +181,23 @@ __device__ __forceinline__ void emit_channel(const uint32_t* code32, int nvec, v
       }
     } else {
       for (int j = tid; j < nvec; j += T) store_global_u16(out + 2 * j, (uint16_t)pack_nibbles4(code32[j]));
+    }
+  } else if (format == SQUANT_OUT_BF16) {
+    uint16_t* out = static_cast<uint16_t*>(out_base) + (size_t)m * L;
+    if ((reinterpret_cast<uintptr_t>(out) & 7u) == 0) {
+      for (int j = tid; j < nvec; j += T) {
+        const vf4 v = dequant4(code32[j], s);
+        vu2 o;
+        o.x = bf16_bits(v.x) | (bf16_bits(v.y) << 16);
+        o.y = bf16_bits(v.z) | (bf16_bits(v.w) << 16);
+        store_global_u2(out + 4 * j, o);
+      }
+    } else {
+      for (int j = tid; j < nvec; j += T) {
+        const vf4 v = dequant4(code32[j], s);
+        out[4 * j] = (uint16_t)bf16_bits(v.x); out[4 * j + 1] = (uint16_t)bf16_bits(v.y);
+        out[4 * j + 2] = (uint16_t)bf16_bits(v.z); out[4 * j + 3] = (uint16_t)bf16_bits(v.w);
+      }
     }
   } else {  // SQUANT_OUT_F32
     float* out = static_cast<float*>(out_base) + (size_t)m * L;
@@ -205,6 +236,9 @@ __device__ __forceinline__ void emit_channel_bytes(const int8_t* code, int L, vo
       const uint32_t hi = (2 * j + 1 < L) ? ((uint32_t)code[2 * j + 1] & 0xFu) : 0u;
       out[j] = (uint8_t)(lo | (hi << 4));
     }
+  } else if (format == SQUANT_OUT_BF16) {
+    uint16_t* out = static_cast<uint16_t*>(out_base) + (size_t)m * L;
+    for (int j = tid; j < L; j += T) out[j] = (uint16_t)bf16_bits((float)code[j] * s);
   } else {  // SQUANT_OUT_F32
     float* out = static_cast<float*>(out_base) + (size_t)m * L;
     for (int j = tid; j < L; j += T) out[j] = (float)code[j] * s;

@@ -95,6 +95,7 @@ def test_output_bytes_and_format_checks(L):
     assert L.squant_output_bytes(4, 3, 3, 3, 1) == 4 * 14      # odd rows round up
     assert L.squant_output_bytes(4, 4, 3, 3, 1) == 4 * 18
     assert L.squant_output_bytes(4, 3, 3, 3, 2) == 4 * 27 * 4
+    assert L.squant_output_bytes(4, 3, 3, 3, 3) == 4 * 27 * 2
     assert L.squant_output_bytes(4, 3, 3, 3, 7) == 0
     assert L.squant_output_bytes(0, 3, 3, 3, 0) == 0
     p = ctypes.c_void_p(0x1000)
@@ -108,7 +109,8 @@ def test_output_bytes_and_format_checks(L):
     assert q(p, 0, 4, 4, 3, 3, 4, 5, 0, p, p, None) == 4
     assert q(p, 3, 4, 4, 3, 3, 4, 2, 0, p, p, None) == 8       # unknown weight type
     assert q(p, -1, 4, 4, 3, 3, 4, 2, 0, p, p, None) == 8
-    assert q(p, 0, 4, 4, 3, 3, 4, 2, 3, p, p, None) == 8       # unknown output format
+    assert q(p, 0, 4, 4, 3, 3, 4, 2, 4, p, p, None) == 8       # unknown output format
+    assert q(p, 0, 4, 4, 3, 3, 4, 2, 3, ctypes.c_void_p(0x1001), p, None) == 8  # bfloat16 output off 2 bytes
     assert q(ctypes.c_void_p(0x1002), 0, 4, 4, 3, 3, 4, 2, 0, p, p, None) == 8   # float weights off 4 bytes
     assert q(p, 0, 4, 4, 3, 3, 4, 2, 2, ctypes.c_void_p(0x1002), p, None) == 8  # float output off 4 bytes
     from paper_2202_07471_amd.binding import squant_tensor_t

@@ -38,11 +38,17 @@ def expected(w, bits, mode, output, sq):
         return oracle.pack_int4(codes), scales
     if output == sq.OUT_F32:
         return oracle.dequantize(codes, scales), scales
+    if output == sq.OUT_BF16:
+        return oracle.dequantize_bf16(codes, scales), scales
     return codes, scales
 
 
 def check(got, got_s, want, want_s, what):
+    if got.dtype == torch.bfloat16:
+        got = got.view(torch.int16)
     got, got_s = got.cpu().numpy(), got_s.cpu().numpy()
+    if got.dtype == np.int16:
+        got = got.view(np.uint16)
     assert np.array_equal(got_s.view(np.uint32), want_s.view(np.uint32)), f"scales differ {what}"
     assert got.shape == want.shape and got.dtype == want.dtype, (what, got.shape, want.shape)
     a = got.view(np.uint32) if got.dtype == np.float32 else got
@@ -85,6 +91,17 @@ def test_dequantised_f32(sq, shape, kind):
         check(got, got_s, want, want_s, f"f32 {shape} {kind} bits={bits} mode={mode}")
 
 
+@pytest.mark.parametrize("kind", ["normal", "grid"])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_dequantised_bf16(sq, shape, kind):
+    w = weights(shape, 37 + sum(shape), kind)
+    for bits, mode in ((4, 2), (8, 2)):
+        want, want_s = expected(w, bits, mode, sq.OUT_BF16, sq)
+        got, got_s = sq.squant_quantize_ex(torch.from_numpy(w).cuda(), bits, mode, sq.OUT_BF16)
+        torch.cuda.synchronize()
+        check(got, got_s, want, want_s, f"bf16 {shape} {kind} bits={bits} mode={mode}")
+
+
 @pytest.mark.parametrize("shape", [(6, 64, 3, 3), (9, 512, 1, 1), (8, 5, 3, 3)])
 def test_output_buffers_off_16_byte_alignment(sq, shape):
     """Rows that do not start on 16 bytes take the kernels' narrow-store paths."""
@@ -93,6 +110,7 @@ def test_output_buffers_off_16_byte_alignment(sq, shape):
     n = w.size
     for output, dtype, elems, off in ((sq.OUT_INT4, torch.uint8, shape[0] * ((n // shape[0] + 1) // 2), 4),
                                       (sq.OUT_F32, torch.float32, n, 1),
+                                      (sq.OUT_BF16, torch.bfloat16, n, 1),
                                       (sq.OUT_INT8, torch.int8, n, 4)):
         big = torch.zeros(elems + 64, dtype=dtype, device="cuda")
         out = big[off:off + elems]
@@ -104,7 +122,7 @@ def test_output_buffers_off_16_byte_alignment(sq, shape):
         assert (big[:off] == 0).all() and (big[off + elems:] == 0).all()   # nothing written outside
 
 
-@pytest.mark.parametrize("output", ["int4", "f32"])
+@pytest.mark.parametrize("output", ["int4", "f32", "bf16"])
 def test_layer_set_batched_formats(sq, output):
     specs = synth.config_specs(2)
     ws = [synth.generate(s) for s in specs]

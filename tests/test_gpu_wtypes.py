@@ -113,3 +113,35 @@ def test_mixed_dtypes_in_one_batch_are_refused(sq):
     a = torch.zeros((4, 4, 3, 3), device="cuda")
     with pytest.raises(ValueError):
         sq.BatchPlan([a, a.half()])
+
+
+def test_config5_full_size_bf16_to_packed_int4_sampled(sq):
+    """The benchmark's 256 x [512,512,3,3] workload with bfloat16 weights and packed 4-bit
+    output in one batched call; the reference checks sampled whole tensors and channels."""
+    specs = synth.config_specs(5)
+    shape = specs[0].shape
+    rng = np.random.default_rng(2)
+    sample_tensors = {3, 200}
+    sample_channels = {int(t): sorted(set(int(c) for c in rng.integers(0, shape[0], 2)))
+                       for t in rng.choice(256, 24, replace=False)}
+    keep, dws = {}, []
+    buf = np.empty(shape, np.float32)
+    for s in specs:
+        w = synth.generate(s, out=buf)
+        d16 = torch.from_numpy(w).cuda().to(torch.bfloat16)
+        if s.index in sample_tensors or s.index in sample_channels:
+            keep[s.index] = d16.cpu().view(torch.int16).numpy().view(np.uint16)
+        dws.append(d16)
+    outs, scales = sq.squant_quantize_batched_ex(dws, 4, 2, sq.OUT_INT4)
+    torch.cuda.synchronize()
+    row = shape[1] * shape[2] * shape[3] // 2
+    for t in sample_tensors:
+        codes, want_s = oracle.quantize(oracle.widen(keep[t], "bf16"), 4, 2, threads=8)
+        assert np.array_equal(outs[t].cpu().numpy(), oracle.pack_int4(codes)), f"tensor {t}"
+        assert np.array_equal(scales[t].cpu().numpy().view(np.uint32), want_s.view(np.uint32))
+    for t, chans in sample_channels.items():
+        for c in chans:
+            codes, want_s = oracle.quantize(oracle.widen(keep[t][c][None], "bf16"), 4, 2)
+            got = outs[t][c].cpu().numpy()
+            assert got.shape == (row,) and np.array_equal(got, oracle.pack_int4(codes)[0]), (t, c)
+            assert scales[t][c].cpu().numpy().view(np.uint32) == want_s.view(np.uint32)[0]

@@ -27,3 +27,13 @@ def test_reciprocal_division_is_exact_on_every_near_midpoint_case(tmp_path):
     assert "mismatches=0" in out.stdout
     cases = int(out.stdout.split("near_midpoint_cases=")[1].split()[0])
     assert cases > 60_000_000
+
+
+def test_variant_choice_covers_every_shape(tmp_path):
+    exe = str(tmp_path / "host_plan_check")
+    subprocess.check_call(["g++", "-std=c++17", "-O2",
+                           "-I", os.path.join(ROOT, "paper_2202_07471_amd", "csrc"),
+                           os.path.join(ROOT, "tests", "host_plan_check.cpp"), "-o", exe])
+    out = subprocess.run([exe], capture_output=True, text=True)
+    assert out.returncode == 0, out.stdout + out.stderr
+    assert "plan_mismatches=0" in out.stdout

@@ -72,3 +72,26 @@ def test_widen_bf16_all_patterns_against_bit_shift():
     nan = np.isnan(want)
     assert np.array_equal(np.isnan(got), nan)
     assert np.array_equal(got.view(np.uint32)[~nan], want.view(np.uint32)[~nan])
+
+
+def test_dequantize_bf16_against_torch_and_tie_cases():
+    torch = pytest.importorskip("torch")
+    rng = np.random.default_rng(3)
+    codes = rng.integers(-127, 128, (16, 999)).astype(np.int8)
+    scales = (rng.random(16) * 0.02 + 1e-5).astype(np.float32)
+    got = oracle.dequantize_bf16(codes, scales)
+    f32 = oracle.dequantize(codes, scales)
+    want = torch.from_numpy(f32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(got, want)
+    # exact ties: code * scale with scale a power of two is exact, and codes whose low bits
+    # end in ...1000 0000 after the 8 kept significand bits sit exactly between two bfloat16
+    codes = np.array([[-127, -125, 125, 127, 3, 1, 0, 126, 124]], np.int8)   # 127 = 1111111b: 8 bits fit
+    scales = np.array([2.0 ** -9 * (1 + 2.0 ** -8)], np.float32)            # forces 9+ significand bits
+    got = oracle.dequantize_bf16(codes, scales)
+    want = torch.from_numpy(oracle.dequantize(codes, scales)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(got, want)
+    # a hand-made tie: 1 + 2^-8 lies exactly between bfloat16 1.0 (even) and 1 + 2^-7
+    assert oracle.dequantize_bf16(np.array([[1]], np.int8), np.array([1 + 2.0 ** -8], np.float32))[0, 0] == 0x3F80
+    # 1 + 3 * 2^-8 lies between 1 + 2^-7 (odd) and 1 + 2^-6 (even): goes up
+    assert oracle.dequantize_bf16(np.array([[1]], np.int8), np.array([1 + 3 * 2.0 ** -8], np.float32))[0, 0] == 0x3F82
+    assert oracle.dequantize_bf16(np.array([[-1]], np.int8), np.array([1 + 3 * 2.0 ** -8], np.float32))[0, 0] == 0xBF82
