@@ -196,15 +196,15 @@ def main() -> int:
         # the GPU result of the timed configuration, checked against the same reference
         mism = 0
         for i, (rc, rs) in enumerate(ref):
-            gc = plan.codes[i].cpu().numpy()
+            go = plan.codes[i]
+            gc = (go.view(torch.int16) if go.dtype == torch.bfloat16 else go).cpu().numpy()
             gs = plan.scales[i].cpu().numpy()
             if args.output == "int4":
                 rc = oracle.pack_int4(rc)
             elif args.output == "f32":
                 rc, gc = oracle.dequantize(rc, rs).view(np.uint32), gc.view(np.uint32)
             elif args.output == "bf16":
-                rc = oracle.dequantize_bf16(rc, rs)
-                gc = plan.codes[i].view(torch.int16).cpu().numpy().view(np.uint16)
+                rc, gc = oracle.dequantize_bf16(rc, rs), gc.view(np.uint16)
             mism += int((gc != rc).sum()) + int((gs.view(np.uint32) != rs.view(np.uint32)).sum())
         cpu_baseline = {"value": round(sample_params / cpu_s / 1e9, 5), "unit": "Gparams/s",
                         "cores": threads, "kind": "oracle",
