@@ -140,7 +140,9 @@ int squant_quantize_batched_ex(const squant_tensor_t* h_tensors, int32_t n_tenso
                                squant_output_t output, void* d_workspace, size_t workspace_bytes,
                                void* stream);
 
-/* Largest cin*kh*kw one output channel may have (device dependent; 0 on error). */
+/* Largest cin*kh*kw one output channel may have (device dependent; 0 on error).  The figure
+ * is for 16-byte aligned weights with cin a multiple of 4; for 1x1 and 3x3 kernels other
+ * tensors go through the generic kernel, which holds more per element and takes less. */
 int64_t squant_max_channel_elems(int32_t kh, int32_t kw);
 
 /* Measurement aid (opt-in, per calling thread; the only state the library keeps).

@@ -126,6 +126,11 @@ Plan plan_tensor(const void* w, const void* out, int64_t N, int64_t K, int lds_l
       const int nv = variant == kK1x1 ? 1 : variant == kK1x2 ? 2 : variant == kK1x4 ? 4 : 8;
       return Plan{variant, (int)round_up64((N / 4 + nv - 1) / nv), round_up((size_t)N, 16)};
     }
+    case kK1Stream: {
+      const size_t lds = round_up((size_t)N, 16);  // the channel's int8 codes
+      if (lds + sizeof(K9Shared) + 64 > (size_t)lds_limit) return Plan{kK1Stream, 0, 0};
+      return Plan{kK1Stream, 1024, lds};
+    }
     default: break;
   }
   const size_t lds = generic_lds_bytes(N, K);
@@ -136,7 +141,8 @@ Plan plan_tensor(const void* w, const void* out, int64_t N, int64_t K, int lds_l
 // Whether a tensor may join a launch of the mixed kernel: its variant is one the mixed kernel
 // carries (all but the eight-vector 1x1 variant) and fits its workgroup size and LDS.
 bool mixable(const Plan& p, size_t lds_cap) {
-  return p.variant != kK1x8 && p.threads <= kMixedMaxThreads && p.lds <= lds_cap;
+  return p.variant != kK1x8 && p.variant != kK1Stream && p.threads <= kMixedMaxThreads &&
+         p.lds <= lds_cap;
 }
 
 int launch_group(const Group& g, const TensorDesc* d_table, int qmax, int mode, int output,
@@ -178,6 +184,8 @@ int launch_group(const Group& g, const TensorDesc* d_table, int qmax, int mode, 
   static const kernel_t k1x4[4] = SQ_K1_ROW(256, 4);
   static const kernel_t k1x8[4] = SQ_K1_ROW(1024, 8);
 #undef SQ_K1_ROW
+  static const kernel_t k1s[4] = {squant_channel_k1_stream<SQUANT_MODE_E>, squant_channel_k1_stream<SQUANT_MODE_E>,
+                                  squant_channel_k1_stream<SQUANT_MODE_EKC>, squant_channel_k1_stream<SQUANT_MODE_EKC>};
   static const kernel_t mixed[4] = {squant_channel_mixed<SQUANT_MODE_E>, squant_channel_mixed<SQUANT_MODE_EK>,
                                     squant_channel_mixed<SQUANT_MODE_EKC>, squant_channel_mixed<SQUANT_MODE_EC>};
   const kernel_t kernel = (g.variant == kMixed || g.variant == kMixedWave) ? mixed[mode]
@@ -185,6 +193,7 @@ int launch_group(const Group& g, const TensorDesc* d_table, int qmax, int mode, 
                           : g.variant == kK1x2 ? k1x2[mode]
                           : g.variant == kK1x4 ? k1x4[mode]
                           : g.variant == kK1x8 ? k1x8[mode]
+                          : g.variant == kK1Stream ? k1s[mode]
                           : g.variant == kK9x1 ? k9x1[mode]
                           : g.variant == kK9x2 ? k9x2[mode]
                           : g.variant == kK9x4 ? (g.threads <= 256 ? k9x4[mode] : k9x4_large[mode])
@@ -374,8 +383,12 @@ int64_t squant_max_channel_elems(int32_t kh, int32_t kw) {
   // largest N with generic_lds_bytes(N, K) + static <= limit
   const int64_t budget = (int64_t)lim.lds_bytes - kStaticLds - 16 - 3;
   const int64_t per_kernel = 5 * K + (K == 1 ? 0 : 8);
-  const int64_t n = budget / per_kernel;
-  return n > 0 ? n * K : 0;
+  int64_t n = budget / per_kernel;
+  if (n < 0) n = 0;
+  // the specialised kernels (16-byte aligned weights, cin a multiple of 4) hold less per element
+  if (K == 9) n = std::max<int64_t>(n, kMaxK9Cin);
+  if (K == 1) n = std::max<int64_t>(n, ((int64_t)lim.lds_bytes - (int64_t)sizeof(K9Shared) - 64) / 16 * 16);
+  return n * K;
 }
 
 int squant_kernel_timer_enable(int32_t slots) {
@@ -426,6 +439,6 @@ const char* squant_status_string(int status) {
   }
 }
 
-int squant_version(void) { return 119; }
+int squant_version(void) { return 120; }
 
 }  // extern "C"

@@ -339,4 +339,228 @@ __global__ void __launch_bounds__(MAX_THREADS)
   k1_channel<MODE, NV>(a, d, m, smem, sh);
 }
 
+// ---------------------------------------------------------------------------
+// Streaming variant for channels too long for the register-resident kernel above
+// (cin > 32768, e.g. the input side of a very wide fully connected layer).  Only the
+// channel's codes live on chip (cin bytes of LDS); the weights are walked three times or
+// more - absmax, SQuant-E with the histogram, then every step of the selection - and each
+// walk recomputes the element's perturbation from the weight, which gives the same bits
+// every time.  The re-reads come from the caches (one channel is a few hundred KB).
+// Same selection as k1_channel_stage, with "the elements still undecided" expressed as a
+// prefix of u = P or ~P instead of a per-thread bit mask.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ int32_t k1_round(float wv, float s, float rs, bool fast, float qmaxf,
+                                            float& c) {
+  const float x = fast ? div_by_reciprocal(wv, s, rs) : wv / s;  // the IEEE quotient either way
+  const float xc = __builtin_amdgcn_fmed3f(x, -qmaxf, qmaxf);
+  c = rintf(xc);
+  const float p = c - xc;  // exact
+  return __float_as_int(__builtin_fmaf(p, 8388608.0f, 12582912.0f)) - 0x4B400000;
+}
+
+// Sum of one count per thread over the workgroup (LDS counter, three barriers).
+__device__ __forceinline__ uint32_t block_count(SelectShared& sh, uint32_t mine) {
+  __syncthreads();
+  if (threadIdx.x == 0) sh.wave_cnt[16] = 0;
+  __syncthreads();
+  if (mine) atomicAdd(&sh.wave_cnt[16], mine);
+  __syncthreads();
+  return sh.wave_cnt[16];
+}
+
+template <int MODE>
+__device__ __forceinline__ void k1_stream_channel(const LaunchArgs& a, const TensorDesc& d, int m,
+                                                  unsigned char* smem, K9Shared& sh) {
+  constexpr bool kChannelStage = MODE == SQUANT_MODE_EKC || MODE == SQUANT_MODE_EC;
+  const int T = blockDim.x, tid = threadIdx.x;
+  const float qmaxf = (float)a.qmax;
+  uint32_t* code32 = reinterpret_cast<uint32_t*>(smem);
+  const int N = d.N, nvec = N >> 2;  // cin % 4 == 0
+  const int wtype = a.wtype;
+  const void* wbase = d.w;
+  const size_t chan = (size_t)m * N;
+  auto load4 = [&](int idx, float (&w)[4]) {
+    if (wtype == SQUANT_W_F32) {
+      const vf4 v = load_global_f4(static_cast<const float*>(wbase) + chan + 4 * (size_t)idx);
+      w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+    } else {
+      const uint32_t* p = reinterpret_cast<const uint32_t*>(static_cast<const uint16_t*>(wbase) + chan +
+                                                            4 * (size_t)idx);
+      const bool bf16 = wtype == SQUANT_W_BF16;
+      widen_pair(load_global_u1(p), bf16, w[0], w[1]);
+      widen_pair(load_global_u1(p + 1), bf16, w[2], w[3]);
+    }
+  };
+
+  if (kChannelStage) { select_reset(sh.sel); k1_list_reset(sh.sel); }  // before the first barrier
+  float amax = 0.0f;
+  for (int idx = tid; idx < nvec; idx += T) {
+    float w[4];
+    load4(idx, w);
+    amax = fmaxf(fmaxf(fmaxf(amax, fabsf(w[0])), fabsf(w[1])), fmaxf(fabsf(w[2]), fabsf(w[3])));
+  }
+  amax = block_max_dpp1(amax, sh.red_f);
+  const float s = amax > 0.0f ? amax / qmaxf : 1.0f;
+  if (tid == 0) d.scales[m] = s;
+  const bool fast = amax >= 0x1p-60f && amax <= 0x1p60f;  // uniform over the workgroup
+  const float rs = 1.0f / s;
+
+  // ---- SQuant-E: codes to LDS, perturbations into the level-0 histogram ----
+  int64_t esum = 0;
+  for (int idx = tid; idx < nvec; idx += T) {
+    float w[4];
+    load4(idx, w);
+    uint32_t packed = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float c;
+      const int32_t P = k1_round(w[e], s, rs, fast, qmaxf, c);
+      packed = __builtin_amdgcn_cvt_pk_u8_f32(c + 128.0f, e, packed);
+      if (kChannelStage) { k1_count(sh.sel, P); esum += P; }
+    }
+    code32[idx] = packed;
+  }
+
+  if (kChannelStage) {
+    const int64_t ec = block_sum(esum, sh.red_i);  // its barriers publish codes and histogram
+    const int sgn = sign_of(ec);
+    const int64_t kc = flips_for(ec < 0 ? -ec : ec);
+    uint32_t need = (uint32_t)(kc > N ? N : kc);
+    const int32_t smask = sgn < 0 ? -1 : 0;
+    // f(u, n) for every element n of the channel, u = P (sum > 0) or ~P (sum < 0): the wanted
+    // side has u > 0 resp. u >= 0, larger u is the better candidate
+    auto for_each = [&](auto&& f) {
+      for (int idx = tid; idx < nvec; idx += T) {
+        float w[4];
+        load4(idx, w);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          float c;
+          f(k1_round(w[e], s, rs, fast, qmaxf, c) ^ smask, 4 * idx + e);
+        }
+      }
+    };
+    auto eligible = [&](int32_t u) { return u > 0 || (smask != 0 && u == 0); };
+    do {  // once; `break` leaves the selection
+      if (kc <= 0) break;
+      uint32_t count = 0, need_at = 0;
+      const int dtop = k1_scan_top(sh.sel.hist, sgn, need, need_at, count);
+      if (dtop < 0) {  // fewer candidates of the wanted sign than flips wanted: all of them flip
+        for_each([&](int32_t u, int n) { if (eligible(u)) flip_code(code32, n, sgn); });
+        break;
+      }
+      need = need_at;
+      const int32_t thr_member = dtop << 15, thr_flip = (dtop + 1) << 15;
+      if (sgn > 0 && dtop == 0) {  // the bin that P = 0 shares: count its real members
+        uint32_t mine = 0;
+        for_each([&](int32_t u, int) { mine += (u > 0 && u < thr_flip) ? 1u : 0u; });
+        count = block_count(sh.sel, mine);
+        if (count < need) need = count;
+      }
+      if (count == need) {  // everything from the boundary bin up flips
+        for_each([&](int32_t u, int n) { if (u >= thr_member && eligible(u)) flip_code(code32, n, sgn); });
+        break;
+      }
+      if (count <= (uint32_t)kListCap) {
+        for_each([&](int32_t u, int n) {
+          if (u >= thr_member) {
+            if (u >= thr_flip) flip_code(code32, n, sgn);
+            else if (eligible(u)) k1_push(sh.sel, (uint32_t)u, n);
+          }
+        });
+        __syncthreads();
+        k1_rank_list(sh.sel, count, need, sgn, code32);
+        break;
+      }
+      // a crowded bin: flip what lies above it, then histogram passes over the lower bits.
+      // Members are the eligible elements with (u >> pshift) == prefix.
+      for_each([&](int32_t u, int n) { if (u >= thr_flip) flip_code(code32, n, sgn); });
+      int32_t prefix = dtop;
+      int pshift = 15;
+      while (count > (uint32_t)kListCap && count != need && pshift > 0) {
+        const int shift = pshift == 15 ? 7 : 0;
+        __syncthreads();  // every wave has finished reading the histogram
+        for (int b = tid; b < 256; b += T) sh.sel.hist[b] = 0;
+        __syncthreads();
+        for_each([&](int32_t u, int) {
+          if ((u >> pshift) == prefix && eligible(u)) atomicAdd(&sh.sel.hist[((uint32_t)u >> shift) & 255u], 1u);
+        });
+        __syncthreads();
+        const uint32_t d2 = scan_histogram_top(sh.sel.hist, need, need_at, count);
+        need = need_at;
+        for_each([&](int32_t u, int n) {
+          if ((u >> pshift) == prefix && eligible(u) && (((uint32_t)u >> shift) & 255u) > d2)
+            flip_code(code32, n, sgn);
+        });
+        // bits 14..7 join the prefix; the last pass (bits 7..0, bit 7 shared) pins u itself
+        prefix = shift == 7 ? (prefix << 8) | (int32_t)d2 : ((prefix >> 1) << 8) | (int32_t)d2;
+        pshift = shift;
+      }
+      if (count == need) {
+        for_each([&](int32_t u, int n) {
+          if ((u >> pshift) == prefix && eligible(u)) flip_code(code32, n, sgn);
+        });
+        break;
+      }
+      if (count <= (uint32_t)kListCap) {
+        for_each([&](int32_t u, int n) {
+          if ((u >> pshift) == prefix && eligible(u)) k1_push(sh.sel, (uint32_t)u, n);
+        });
+        __syncthreads();
+        k1_rank_list(sh.sel, count, need, sgn, code32);
+        break;
+      }
+      // more than kListCap elements equal in all their bits: the lowest indices flip.  Within
+      // one step of the walk, element order is thread order.
+      const int lane = tid & (kWave - 1), wid = tid / kWave;
+      const int nw = (T + kWave - 1) / kWave;
+      uint32_t done = 0;
+      for (int base = 0; base < nvec && done < need; base += T) {
+        const int idx = base + tid;
+        uint32_t bits = 0;
+        if (idx < nvec) {
+          float w[4];
+          load4(idx, w);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            float c;
+            const int32_t u = k1_round(w[e], s, rs, fast, qmaxf, c) ^ smask;
+            bits |= ((u >> pshift) == prefix && eligible(u)) ? 1u << e : 0u;
+          }
+        }
+        const uint32_t mine = (uint32_t)__popc(bits);
+        const uint32_t incl = wave_prefix_sum(mine);
+        __syncthreads();
+        if (lane == kWave - 1) sh.sel.wave_cnt[wid] = incl;
+        __syncthreads();
+        uint32_t rank = done + incl - mine, total = 0;
+        for (int w2 = 0; w2 < nw; ++w2) {
+          const uint32_t c = sh.sel.wave_cnt[w2];
+          if (w2 < wid) rank += c;
+          total += c;
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (bits & (1u << e)) {
+            if (rank < need) flip_code(code32, 4 * idx + e, sgn);
+            ++rank;
+          }
+        done += total;
+      }
+    } while (false);
+  }
+  __syncthreads();
+
+  emit_channel(code32, nvec, d.out, m, s, a.out_format, tid, T);
+}
+
+template <int MODE>
+__global__ void __launch_bounds__(1024) squant_channel_k1_stream(LaunchArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];  // N bytes of biased codes
+  __shared__ K9Shared sh;
+  int m;
+  const TensorDesc d = locate(a, blockIdx.x, m);
+  k1_stream_channel<MODE>(a, d, m, smem, sh);
+}
+
 }  // namespace squant

@@ -12,7 +12,8 @@ namespace squant {
 enum Variant {
   kGeneric = 0,
   kK9x1 = 1, kK9x2 = 2, kK9x4 = 3,             // 3x3 kernels per thread: 1, 2, 4
-  kK1x1 = 4, kK1x2 = 5, kK1x4 = 6, kK1x8 = 7  // 1x1 / FC: 16-byte vectors per thread: 1, 2, 4, 8
+  kK1x1 = 4, kK1x2 = 5, kK1x4 = 6, kK1x8 = 7,  // 1x1 / FC: 16-byte vectors per thread: 1, 2, 4, 8
+  kK1Stream = 8                                // 1x1 / FC beyond kMaxK1Cin: weights walked repeatedly
 };
 
 constexpr int kMaxK9Cin = 4096;   // 3x3 variant: cin % 4 == 0 up to here
@@ -20,11 +21,13 @@ constexpr int kMaxK1Cin = 32768;  // 1x1 variant: cin % 4 == 0 up to here
 
 SQ_HD int64_t round_up64(int64_t v) { return (v + 63) / 64 * 64; }
 
-// Kernel family of a tensor: 9 = the 3x3 kernel, 1 = the 1x1 / FC kernel, 0 = generic.
+// Kernel family of a tensor: 9 = the 3x3 kernel, 1 = the 1x1 / FC kernel, 2 = the streaming
+// 1x1 / FC kernel, 0 = generic.
 // aligned: weights on 16 bytes and output on 4 (what the vector loads / stores need)
 SQ_HD int choose_family(int64_t N, int64_t K, bool aligned) {
   if (K == 9 && (N & 3) == 0 && N <= kMaxK9Cin && aligned) return 9;
   if (K == 1 && (N & 3) == 0 && N <= kMaxK1Cin && aligned) return 1;
+  if (K == 1 && (N & 3) == 0 && aligned) return 2;
   return 0;
 }
 
@@ -52,6 +55,7 @@ SQ_HD int choose_variant(int64_t N, int64_t K, bool aligned) {
     const int64_t nvec = N / 4;
     return nvec <= 64 ? kK1x1 : nvec <= 128 ? kK1x2 : nvec <= 1024 ? kK1x4 : kK1x8;
   }
+  if (family == 2) return kK1Stream;
   return kGeneric;
 }
 

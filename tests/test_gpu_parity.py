@@ -235,10 +235,42 @@ def test_config5_full_size_sampled(sq):
         assert bool((scales[t] > 0).all())
 
 
+# ---------------------------------------------------------------------------
+# very long 1x1 / FC channels: the streaming kernel (cin beyond 32768)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("kind", ["normal", "heavy", "grid"])
+@pytest.mark.parametrize("shape", [(3, 32772, 1, 1), (2, 40000, 1, 1), (2, 65536, 1, 1), (1, 131072, 1, 1)])
+def test_streaming_kernel_for_long_channels(sq, shape, kind):
+    w = rand_weights(shape, 900 + shape[1] % 97, kind)
+    if kind == "normal":
+        w[0, 5::7] = 0.0          # plenty of exact zeros next to the small positive perturbations
+    for bits, mode in ((4, 2), (8, 2), (3, 0), (2, 3)):
+        codes, scales = run_single(sq, w, bits, mode)
+        assert_same(codes, scales, w, bits, mode, what=f"stream {shape} {kind} bits={bits} mode={mode}")
+
+
+def test_streaming_kernel_degenerate_channels(sq):
+    """Channels whose perturbations are all equal, all zero, or all on one side."""
+    n = 36000
+    rows = [np.full(n, 0.3, np.float32), np.zeros(n, np.float32), np.full(n, -1.0, np.float32)]
+    half = np.full(n, 2.5, np.float32); half[0] = 7.0            # x = 2.5 everywhere: exact halves
+    tiny = np.full(n, 0.01, np.float32); tiny[0] = 7.0           # every element rounds to 0, p < 0 ... same sign
+    third = np.full(n, 7.0 / 3.0, np.float32); third[0] = 7.0
+    w = np.stack(rows + [half, tiny, third])[:, :, None, None]
+    for bits in (4, 8):
+        codes, scales = run_single(sq, w, bits, 2)
+        assert_same(codes, scales, w, bits, 2, what=f"stream degenerate bits={bits}")
+
+
 def test_oversize_channel_is_an_error(sq):
     limit = sq.squant_max_channel_elems(1, 1)
-    assert limit >= 16384
+    assert limit >= 131072
     w = torch.zeros(1, limit + 4096, 1, 1, device="cuda")
+    with pytest.raises(sq.SQuantError) as e:
+        sq.squant_quantize(w, 4, 2)
+    assert e.value.status == 7
+    assert sq.squant_max_channel_elems(3, 3) >= 9 * 4096
+    w = torch.zeros(1, 20000, 3, 3, device="cuda")
     with pytest.raises(sq.SQuantError) as e:
         sq.squant_quantize(w, 4, 2)
     assert e.value.status == 7

@@ -109,6 +109,21 @@ def test_layer_set_batched_sixteen_bit(sq, wtype, output):
         assert np.array_equal(got.reshape(want.shape), want), f"batched {wtype} {output} {s.shape}"
 
 
+@pytest.mark.parametrize("wtype,output", [("f16", "int4"), ("bf16", "bf16")])
+def test_streaming_kernel_sixteen_bit_and_formats(sq, wtype, output):
+    shape = (2, 50000, 1, 1)
+    t16, bits = to16(weights(shape, 77, "normal"), wtype)
+    codes, want_s = oracle.quantize(oracle.widen(bits, wtype), 4, 2, threads=8)
+    got, got_s = sq.squant_quantize_ex(t16.cuda(), 4, 2, sq.OUTPUTS[output])
+    torch.cuda.synchronize()
+    assert np.array_equal(got_s.cpu().numpy().view(np.uint32), want_s.view(np.uint32))
+    if output == "int4":
+        assert np.array_equal(got.cpu().numpy(), oracle.pack_int4(codes))
+    else:
+        want = oracle.dequantize_bf16(codes, want_s)
+        assert np.array_equal(got.view(torch.int16).cpu().numpy().view(np.uint16).reshape(want.shape), want)
+
+
 def test_mixed_dtypes_in_one_batch_are_refused(sq):
     a = torch.zeros((4, 4, 3, 3), device="cuda")
     with pytest.raises(ValueError):
