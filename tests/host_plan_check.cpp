@@ -10,7 +10,7 @@
 using namespace squant;
 
 int main() {
-  long bad = 0, k9 = 0, k1 = 0, generic = 0;
+  long bad = 0, k9 = 0, k1 = 0, stream = 0, generic = 0;
   for (int aligned = 0; aligned < 2; ++aligned)
     for (int64_t K : {1, 2, 4, 9, 25, 49})
       for (int64_t N = 1; N <= 40000; N += (N < 600 ? 1 : 61)) {
@@ -38,13 +38,16 @@ int main() {
           const int64_t nvec = N / 4, threads = round_up64((nvec + nv - 1) / nv);
           bad += threads * nv < nvec;
           bad += threads > (nv == 8 ? 1024 : 256);
+        } else if (family == 2) {
+          ++stream;  // a 1x1 channel too long for the register-resident kernel
+          bad += v != kK1Stream || K != 1 || !aligned || N % 4 || N <= kMaxK1Cin;
         } else {
           ++generic;
           bad += v != kGeneric;
           bad += aligned && K == 9 && N % 4 == 0 && N <= kMaxK9Cin;
-          bad += aligned && K == 1 && N % 4 == 0 && N <= kMaxK1Cin;
+          bad += aligned && K == 1 && N % 4 == 0;
         }
       }
-  std::printf("plan_mismatches=%ld k9=%ld k1=%ld generic=%ld\n", bad, k9, k1, generic);
+  std::printf("plan_mismatches=%ld k9=%ld k1=%ld stream=%ld generic=%ld\n", bad, k9, k1, stream, generic);
   return bad != 0;
 }
