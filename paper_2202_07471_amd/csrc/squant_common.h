@@ -121,15 +121,20 @@ __device__ __forceinline__ float wave_max_dpp(float v) {
   return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
 }
 
-// sum over the wave of int32 values with |v| <= 2^26 (a row of 16 cannot overflow);
-// uniform 64-bit result
-__device__ __forceinline__ int64_t wave_sum_dpp(int32_t v) {
+// sum over the wave of any int32 values; uniform 64-bit result.  The low 16 bits (unsigned) and
+// the high 16 bits (signed) are added up separately, so no partial sum leaves 32 bits.
+__device__ __forceinline__ int32_t wave_sum_dpp_small(int32_t v) {  // |v| <= 2^24
   v += dpp_i32<0xB1>(v);
   v += dpp_i32<0x4E>(v);
   v += dpp_i32<0x141>(v);
   v += dpp_i32<0x140>(v);
-  return (int64_t)__builtin_amdgcn_readlane(v, 0) + (int64_t)__builtin_amdgcn_readlane(v, 16) +
-         (int64_t)__builtin_amdgcn_readlane(v, 32) + (int64_t)__builtin_amdgcn_readlane(v, 48);
+  return __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) +
+         __builtin_amdgcn_readlane(v, 32) + __builtin_amdgcn_readlane(v, 48);
+}
+__device__ __forceinline__ int64_t wave_sum_dpp(int32_t v) {
+  const int32_t lo = wave_sum_dpp_small(v & 0xFFFF);
+  const int32_t hi = wave_sum_dpp_small(v >> 16);
+  return (int64_t)hi * 65536 + lo;
 }
 
 // Running maximum over the lanes of a wave: lane 63 ends up with the wave's maximum (same

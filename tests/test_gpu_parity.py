@@ -235,6 +235,18 @@ def test_config5_full_size_sampled(sq):
         assert bool((scales[t] > 0).all())
 
 
+@pytest.mark.parametrize("shape", [(3, 492, 3, 3), (2, 512, 3, 3), (2, 8192, 1, 1), (2, 32768, 1, 1), (3, 64, 3, 3)])
+def test_one_sided_perturbations_have_huge_channel_sums(sq, shape):
+    """Every element rounds the same way, so the channel sum reaches thousands of steps: the
+    sums must not wrap, and more flips are wanted than there are candidates."""
+    w = np.full(shape, -1.25, np.float32)
+    w.reshape(shape[0], -1)[:, 0] = 5.0
+    w[0].reshape(-1)[3::11] = 0.61
+    for bits, mode in ((5, 3), (5, 2), (4, 3), (8, 2), (3, 1)):
+        codes, scales = run_single(sq, w, bits, mode)
+        assert_same(codes, scales, w, bits, mode, what=f"one-sided {shape} bits={bits} mode={mode}")
+
+
 # ---------------------------------------------------------------------------
 # very long 1x1 / FC channels: the streaming kernel (cin beyond 32768)
 # ---------------------------------------------------------------------------
