@@ -26,10 +26,12 @@ def sq():
 def random_shape(rng):
     family = rng.integers(0, 4)
     m = int(rng.integers(1, 7))
-    if family == 0:                                   # 3x3, cin % 4 == 0
-        return (m, 4 * int(rng.integers(1, 160)), 3, 3)
-    if family == 1:                                   # 1x1 / FC, cin % 4 == 0
-        return (m, 4 * int(rng.integers(1, 2400)), 1, 1)
+    if family == 0:                                   # 3x3, cin % 4 == 0 (now and then a wide one)
+        hi = 1025 if rng.random() < 0.1 else 160
+        return (m, 4 * int(rng.integers(1, hi)), 3, 3)
+    if family == 1:                                   # 1x1 / FC, cin % 4 == 0 (now and then very long)
+        hi = 12000 if rng.random() < 0.15 else 2400
+        return (min(m, 3), 4 * int(rng.integers(1, hi)), 1, 1)
     if family == 2:                                   # generic kernels
         kh, kw = [(2, 2), (1, 3), (3, 3), (5, 5), (7, 7), (4, 4), (1, 7), (3, 1)][rng.integers(0, 8)]
         n = int(rng.integers(1, 120))
@@ -64,7 +66,7 @@ def random_values(rng, shape):
     return w
 
 
-@pytest.mark.parametrize("block", range(8))
+@pytest.mark.parametrize("block", range(16))
 def test_random_cases(sq, block):
     rng = np.random.default_rng(5000 + block)
     for case in range(60):
@@ -84,6 +86,28 @@ def test_random_cases(sq, block):
             bad = np.argwhere(got != want_c)
             raise AssertionError(f"codes differ: block={block} case={case} shape={shape} bits={bits} "
                                  f"mode={mode}: {len(bad)} elements, first at {bad[0].tolist()}")
+        if case % 3 == 0:                             # the same case through another type / format
+            wtype = ["f16", "bf16"][int(rng.integers(0, 2))]
+            t16 = torch.from_numpy(w).to(torch.float16 if wtype == "f16" else torch.bfloat16)
+            w16 = oracle.widen(t16.view(torch.int16).numpy().view(np.uint16), wtype)
+            if not np.isfinite(w16).all():
+                continue                              # the huge-range pattern leaves binary16
+            want_c, want_s = oracle.quantize(w16, bits, mode, threads=4)
+            fmt = "int4" if bits <= 4 else ["f32", "bf16"][int(rng.integers(0, 2))]
+            print(f"     again as {wtype} -> {fmt}", flush=True)
+            out, scales = sq.squant_quantize_ex(t16.cuda(), bits, mode, sq.OUTPUTS[fmt])
+            torch.cuda.synchronize()
+            assert np.array_equal(scales.cpu().numpy().view(np.uint32), want_s.view(np.uint32)), \
+                f"scales differ ({wtype}): block={block} case={case} shape={shape}"
+            if fmt == "int4":
+                ok = np.array_equal(out.cpu().numpy(), oracle.pack_int4(want_c))
+            elif fmt == "f32":
+                ok = np.array_equal(out.cpu().numpy().view(np.uint32),
+                                    oracle.dequantize(want_c, want_s).view(np.uint32))
+            else:
+                ok = np.array_equal(out.view(torch.int16).cpu().numpy().view(np.uint16),
+                                    oracle.dequantize_bf16(want_c, want_s))
+            assert ok, f"{wtype} -> {fmt} differs: block={block} case={case} shape={shape} bits={bits} mode={mode}"
 
 
 def test_random_batches(sq):
