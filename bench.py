@@ -60,6 +60,17 @@ def load_traffic():
     return None
 
 
+def cpu_model() -> str:
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -169,7 +180,8 @@ def main() -> int:
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "kernel": "squant solver kernel(s) of the batched call",
-                "kernel_ms_avg": round(k_avg_ms, 4), "kernel_ms_min": round(float(np.min(kernel_ms)), 4),
+                "kernel_ms_avg": round(k_avg_ms, 4), "kernel_ms_median": round(float(np.median(kernel_ms)), 4),
+                "kernel_ms_min": round(float(np.min(kernel_ms)), 4),
                 "algorithmic_bytes_per_launch": algo_bytes}
     if os.environ.get("SQUANT_BENCH_TRACE"):
         log("[bench] kernel ms per step: " + " ".join(f"{v:.3f}" for v in kernel_ms))
@@ -211,6 +223,7 @@ def main() -> int:
                         "sample": f"first {len(host_sample)} tensors of the workload "
                                   f"({sample_params} weights), {args.mode}, {threads} threads over output channels",
                         "single_thread_value": round(p1 / cpu1_s / 1e9, 5),
+                        "cpu_model": cpu_model(),
                         "gpu_mismatches_on_sample": mism}
         log(f"[bench] CPU reference: {sample_params / cpu_s / 1e6:.1f} Mparams/s on {threads} threads, "
             f"{p1 / cpu1_s / 1e6:.1f} Mparams/s on 1; GPU mismatches on the sample: {mism}")

@@ -140,6 +140,56 @@ int squant_quantize_batched_ex(const squant_tensor_t* h_tensors, int32_t n_tenso
                                squant_output_t output, void* d_workspace, size_t workspace_bytes,
                                void* stream);
 
+/* Activation ranges without data (Section 4, experimental set-up: a wide, batch-norm based
+ * range per activation tensor, clipped per tensor).  The output of a batch-norm layer is
+ * taken as N(beta_c, gamma_c^2) per channel c, so channel c spans
+ * [beta_c - n_sigma*|gamma_c|, beta_c + n_sigma*|gamma_c|] (each bound: one binary32 multiply,
+ * one add / subtract); the tensor's range is [min_c, max_c] of these, with the lower end (and
+ * the upper, should it be negative) raised to 0 when a ReLU follows.  The uniform quantizer
+ * on that range with 2^bits levels: scale = (hi - lo) / (2^bits - 1) (1.0f for an empty range),
+ * zero_point = round-half-even(-lo / scale) clamped to [0, 2^bits - 1]. */
+typedef struct {
+  const float* gamma;  /* in : device, `channels` binary32 batch-norm weights */
+  const float* beta;   /* in : device, `channels` binary32 batch-norm biases */
+  int32_t channels;
+  int32_t relu;        /* non-zero: a ReLU follows the batch norm */
+} squant_bn_t;
+
+typedef struct {
+  float lo, hi, scale;
+  int32_t zero_point;
+} squant_act_range_t;
+
+/* Device bytes squant_activation_ranges needs for its descriptor table. */
+size_t squant_activation_workspace_bytes(int32_t n_layers);
+
+/* h_layers: HOST array of n_layers descriptors holding DEVICE pointers (reusable as soon as
+ * the call returns); d_ranges: device, n_layers results; d_workspace as for
+ * squant_quantize_batched (at least squant_activation_workspace_bytes, 16-byte aligned).
+ * bits in [2, 16], n_sigma finite and >= 0 (SQUANT_ERR_BITS / SQUANT_ERR_SHAPE otherwise). */
+int squant_activation_ranges(const squant_bn_t* h_layers, int32_t n_layers, float n_sigma,
+                             int32_t bits, squant_act_range_t* d_ranges, void* d_workspace,
+                             size_t workspace_bytes, void* stream);
+
+/* One layer of a network: its weight tensor and, where a batch norm follows it, that
+ * layer's parameters (bn.gamma == NULL: no activation range for this layer). */
+typedef struct {
+  squant_tensor_t weight;
+  squant_bn_t bn;
+} squant_layer_t;
+
+/* Device bytes squant_quantize_network needs. */
+size_t squant_network_workspace_bytes(int32_t n_layers);
+
+/* The data-free pipeline of Section 4 for a whole network in one call: every weight tensor
+ * through the SQuant solver (binary32 weights, int8 codes, as squant_quantize_batched) and
+ * every batch-norm output through squant_activation_ranges, on the same stream.  d_ranges
+ * holds n_layers entries; entry i is written only when layer i has batch-norm parameters. */
+int squant_quantize_network(const squant_layer_t* h_layers, int32_t n_layers, int32_t weight_bits,
+                            squant_mode_t mode, int32_t act_bits, float n_sigma,
+                            squant_act_range_t* d_ranges, void* d_workspace,
+                            size_t workspace_bytes, void* stream);
+
 /* Largest cin*kh*kw one output channel may have (device dependent; 0 on error).  The figure
  * is for 16-byte aligned weights with cin a multiple of 4; for 1x1 and 3x3 kernels other
  * tensors go through the generic kernel, which holds more per element and takes less. */

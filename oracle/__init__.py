@@ -47,6 +47,8 @@ def lib():
         L.squant_oracle_dequantize.argtypes = [vp, vp, i64, i64, vp]
         L.squant_oracle_dequantize_bf16.argtypes = [vp, vp, i64, i64, vp]
         L.squant_oracle_dequantize_bf16.restype = ctypes.c_int
+        L.squant_oracle_activation_range.argtypes = [vp, vp, i64, ctypes.c_float, i32, i32, vp]
+        L.squant_oracle_activation_range.restype = ctypes.c_int
         L.squant_oracle_widen_f16.argtypes = [vp, i64, vp]
         L.squant_oracle_widen_bf16.argtypes = [vp, i64, vp]
         for f in (L.squant_oracle_pack_int4, L.squant_oracle_dequantize,
@@ -162,3 +164,16 @@ def widen(bits16, wtype: str):
     if rc != 0:
         raise ValueError(f"widen failed with status {rc}")
     return out
+
+
+def activation_range(gamma, beta, n_sigma: float, relu: bool, bits: int):
+    """(lo, hi, scale, zero_point) of the batch-norm based per-tensor activation range."""
+    g = np.ascontiguousarray(gamma, dtype=np.float32)
+    b = np.ascontiguousarray(beta, dtype=np.float32)
+    assert g.shape == b.shape and g.ndim == 1
+    out = np.empty(4, dtype=np.float32)
+    rc = lib().squant_oracle_activation_range(g.ctypes.data, b.ctypes.data, g.size, float(n_sigma),
+                                              int(bool(relu)), bits, out.ctypes.data)
+    if rc != 0:
+        raise ValueError(f"squant_oracle_activation_range failed with status {rc}")
+    return np.float32(out[0]), np.float32(out[1]), np.float32(out[2]), int(out[3])

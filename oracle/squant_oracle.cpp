@@ -43,7 +43,9 @@
 // scales and plain rounding, exhaustive 2^K / 2^N flip search for the K and C
 // stages, the constraints of Eq. 6 / 7 / 8, and the flipped-element counts of
 // the appendix table (statistically).  Parity unpinned by the paper (pure
-// conventions, see above): rounding ties, top-k ties, the exact-zero kernel.
+// conventions, see above): rounding ties, top-k ties, the exact-zero kernel, the
+// 4-bit packing layout, and the batch-norm based activation range at the end of
+// this file (the paper names the approach, prints no formula).
 //
 // Build: g++ -std=c++17 -O2 -fno-fast-math -ffp-contract=off -shared -fPIC -pthread
 
@@ -348,6 +350,42 @@ int squant_oracle_widen_bf16(const uint16_t* h, int64_t n, float* out) {
     else v = std::ldexp(128.0 + f, e - 134);
     out[i] = (float)(sign ? -v : v);
   }
+  return 0;
+}
+
+// ---- activation range without data (Section 4, experimental set-up) ----
+// A batch-norm output channel c is taken as N(beta_c, gamma_c^2); the per-tensor range is
+// the union over channels of beta_c -/+ n_sigma * |gamma_c|, cut at 0 from below when a ReLU
+// follows, and the uniform quantizer on it has 2^bits levels.  binary32 throughout, one
+// rounding per arithmetic step, in the order written here.  (The paper only names the
+// approach - a wide batch-norm based range, clipped per tensor; n_sigma and the
+// asymmetric quantizer are this library's reading.)
+// out4 = {lo, hi, scale, zero_point as float}.  Returns 0, or 1 null / 2 bad size / 3 bad bits.
+int squant_oracle_activation_range(const float* gamma, const float* beta, int64_t channels,
+                                   float n_sigma, int32_t relu, int32_t bits, float* out4) {
+  if (!gamma || !beta || !out4) return 1;
+  if (channels <= 0) return 2;
+  if (bits < 2 || bits > 16) return 3;
+  float lo = INFINITY, hi = -INFINITY;
+  for (int64_t c = 0; c < channels; ++c) {
+    const float t = n_sigma * std::fabs(gamma[c]);
+    const float a = beta[c] - t, b = beta[c] + t;
+    if (a < lo) lo = a;
+    if (b > hi) hi = b;
+  }
+  if (relu) {
+    if (lo < 0.0f) lo = 0.0f;
+    if (hi < 0.0f) hi = 0.0f;
+  }
+  lo += 0.0f;  // a zero bound is +0
+  hi += 0.0f;
+  const float q = (float)((1 << bits) - 1);
+  const float span = hi - lo;
+  const float scale = span > 0.0f ? span / q : 1.0f;
+  float z = std::nearbyint(-lo / scale);
+  if (z < 0.0f) z = 0.0f;
+  if (z > q) z = q;
+  out4[0] = lo; out4[1] = hi; out4[2] = scale; out4[3] = z;
   return 0;
 }
 

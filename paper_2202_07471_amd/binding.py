@@ -28,6 +28,20 @@ class squant_tensor_t(ctypes.Structure):
                 ("kw", ctypes.c_int32)]
 
 
+class squant_bn_t(ctypes.Structure):
+    _fields_ = [("gamma", ctypes.c_void_p), ("beta", ctypes.c_void_p), ("channels", ctypes.c_int32),
+                ("relu", ctypes.c_int32)]
+
+
+class squant_act_range_t(ctypes.Structure):
+    _fields_ = [("lo", ctypes.c_float), ("hi", ctypes.c_float), ("scale", ctypes.c_float),
+                ("zero_point", ctypes.c_int32)]
+
+
+class squant_layer_t(ctypes.Structure):
+    _fields_ = [("weight", squant_tensor_t), ("bn", squant_bn_t)]
+
+
 class SQuantError(RuntimeError):
     def __init__(self, status: int, text: str):
         super().__init__(f"squant status {status}: {text}")
@@ -62,6 +76,16 @@ def lib():
         L.squant_quantize_batched_ex.argtypes = [ctypes.POINTER(squant_tensor_t), i32, ctypes.c_int,
                                                  i32, ctypes.c_int, ctypes.c_int, vp, sz, vp]
         L.squant_quantize_batched_ex.restype = ctypes.c_int
+        L.squant_activation_workspace_bytes.argtypes = [i32]
+        L.squant_activation_workspace_bytes.restype = sz
+        L.squant_activation_ranges.argtypes = [ctypes.POINTER(squant_bn_t), i32, ctypes.c_float, i32,
+                                               vp, vp, sz, vp]
+        L.squant_activation_ranges.restype = ctypes.c_int
+        L.squant_network_workspace_bytes.argtypes = [i32]
+        L.squant_network_workspace_bytes.restype = sz
+        L.squant_quantize_network.argtypes = [ctypes.POINTER(squant_layer_t), i32, i32, ctypes.c_int,
+                                              i32, ctypes.c_float, vp, vp, sz, vp]
+        L.squant_quantize_network.restype = ctypes.c_int
         L.squant_max_channel_elems.argtypes = [i32, i32]
         L.squant_max_channel_elems.restype = ctypes.c_int64
         L.squant_status_string.argtypes = [ctypes.c_int]
@@ -236,3 +260,67 @@ def squant_quantize_batched_ex(weights: Iterable[torch.Tensor], bits: int, mode:
     """The batched call for float32 / float16 / bfloat16 weights and any output format."""
     plan = BatchPlan(list(weights), output)
     return plan.run(bits, mode, stream)
+
+
+def _ranges_from(buf: torch.Tensor, n: int):
+    """The device result array (n x {lo, hi, scale, zero_point}) as host tuples."""
+    raw = buf.cpu().numpy().reshape(n, 4)
+    import numpy as np
+    return [(np.float32(r[0]), np.float32(r[1]), np.float32(r[2]), int(r[3:4].view(np.int32)[0]))
+            for r in raw]
+
+
+def squant_activation_ranges(bn_layers, n_sigma: float, bits: int, stream=None):
+    """bn_layers: sequence of (gamma, beta, relu) with float32 device tensors; returns one
+    (lo, hi, scale, zero_point) per layer (synchronises to read the result back)."""
+    layers = list(bn_layers)
+    n = len(layers)
+    desc = (squant_bn_t * max(n, 1))()
+    for i, (g, b, relu) in enumerate(layers):
+        for t in (g, b):
+            _check_weight(t)
+        if g.numel() != b.numel():
+            raise ValueError("gamma and beta differ in length")
+        desc[i] = squant_bn_t(g.data_ptr(), b.data_ptr(), g.numel(), int(bool(relu)))
+    dev = layers[0][0].device if n else torch.device("cuda")
+    out = torch.zeros(max(n, 1) * 4, dtype=torch.float32, device=dev)
+    ws_bytes = int(lib().squant_activation_workspace_bytes(n))
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+    _check(lib().squant_activation_ranges(desc, n, n_sigma, bits, out.data_ptr(), ws.data_ptr(),
+                                          ws_bytes, _stream_ptr(stream)))
+    torch.cuda.synchronize()
+    return _ranges_from(out, n)
+
+
+def squant_quantize_network(layers, weight_bits: int, mode: int = MODE_EKC, act_bits: int = 8,
+                            n_sigma: float = 6.0, stream=None):
+    """layers: sequence of (weight, bn) with bn = None or (gamma, beta, relu).  Returns
+    (codes list, scales list, ranges list with None where a layer has no batch norm)."""
+    layers = list(layers)
+    n = len(layers)
+    dev = layers[0][0].device if n else torch.device("cuda")
+    desc = (squant_layer_t * max(n, 1))()
+    codes, scales = [], []
+    for i, (w, bn) in enumerate(layers):
+        _check_weight(w)
+        cout, cin, kh, kw = _shape4(w)
+        c = torch.empty(w.shape, dtype=torch.int8, device=dev)
+        s = torch.empty(cout, dtype=torch.float32, device=dev)
+        codes.append(c)
+        scales.append(s)
+        wt = squant_tensor_t(w.data_ptr(), c.data_ptr(), s.data_ptr(), cout, cin, kh, kw)
+        if bn is None:
+            desc[i] = squant_layer_t(wt, squant_bn_t(None, None, 0, 0))
+        else:
+            g, b, relu = bn
+            _check_weight(g)
+            _check_weight(b)
+            desc[i] = squant_layer_t(wt, squant_bn_t(g.data_ptr(), b.data_ptr(), g.numel(), int(bool(relu))))
+    out = torch.zeros(max(n, 1) * 4, dtype=torch.float32, device=dev)
+    ws_bytes = int(lib().squant_network_workspace_bytes(n))
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+    _check(lib().squant_quantize_network(desc, n, weight_bits, mode, act_bits, n_sigma, out.data_ptr(),
+                                         ws.data_ptr(), ws_bytes, _stream_ptr(stream)))
+    torch.cuda.synchronize()
+    ranges = _ranges_from(out, n)
+    return codes, scales, [r if layers[i][1] is not None else None for i, r in enumerate(ranges)]

@@ -23,6 +23,7 @@
 #include "squant_k9.h"
 #include "squant_k1.h"
 #include "squant_mixed.h"
+#include "squant_act.h"
 #include "squant_plan.h"
 
 namespace {
@@ -33,6 +34,13 @@ using namespace squant;
 constexpr int kDescChunk = 256;  // 10 KB of by-value kernel arguments per writer launch
 struct DescChunk { TensorDesc t[kDescChunk]; };
 __global__ void write_table(DescChunk c, int count, TensorDesc* table) {
+  const int i = threadIdx.x;
+  if (i < count) table[i] = c.t[i];
+}
+
+constexpr int kBnChunk = 256;
+struct BnChunk { BnDesc t[kBnChunk]; };
+__global__ void write_bn_table(BnChunk c, int count, BnDesc* table) {
   const int i = threadIdx.x;
   if (i < count) table[i] = c.t[i];
 }
@@ -375,6 +383,95 @@ int squant_quantize_batched_ex(const squant_tensor_t* h_tensors, int32_t n_tenso
   return SQUANT_OK;
 }
 
+size_t squant_activation_workspace_bytes(int32_t n_layers) {
+  if (n_layers <= 0) return 0;
+  return (size_t)n_layers * sizeof(BnDesc);
+}
+
+namespace {
+// Shared by squant_activation_ranges and squant_quantize_network: `index[i]` is the entry of
+// d_ranges that layers[i] writes.
+int launch_activation_ranges(const std::vector<BnDesc>& layers, float n_sigma, int32_t bits,
+                             squant_act_range_t* d_ranges, BnDesc* d_table, hipStream_t st) {
+  for (size_t c0 = 0; c0 < layers.size(); c0 += kBnChunk) {
+    BnChunk chunk{};
+    const int cnt = (int)std::min<size_t>(kBnChunk, layers.size() - c0);
+    for (int i = 0; i < cnt; ++i) chunk.t[i] = layers[c0 + i];
+    hipLaunchKernelGGL(write_bn_table, dim3(1), dim3(kBnChunk), 0, st, chunk, cnt, d_table + c0);
+    if (hipGetLastError() != hipSuccess) return SQUANT_ERR_DEVICE;
+  }
+  hipLaunchKernelGGL(squant_activation_range_kernel, dim3((unsigned)layers.size()), dim3(256), 0, st,
+                     d_table, n_sigma, (int32_t)((1 << bits) - 1), d_ranges);
+  if (hipGetLastError() != hipSuccess) return SQUANT_ERR_DEVICE;
+  return SQUANT_OK;
+}
+
+int check_activation_args(int32_t bits, float n_sigma) {
+  if (bits < 2 || bits > 16) return SQUANT_ERR_BITS;
+  if (!(n_sigma >= 0.0f) || !(n_sigma <= 3.0e38f)) return SQUANT_ERR_SHAPE;
+  return SQUANT_OK;
+}
+}  // namespace
+
+int squant_activation_ranges(const squant_bn_t* h_layers, int32_t n_layers, float n_sigma,
+                             int32_t bits, squant_act_range_t* d_ranges, void* d_workspace,
+                             size_t workspace_bytes, void* stream) {
+  if (n_layers < 0) return SQUANT_ERR_SHAPE;
+  if (n_layers == 0) return SQUANT_OK;
+  if (!h_layers || !d_ranges) return SQUANT_ERR_NULL;
+  if (int rc = check_activation_args(bits, n_sigma)) return rc;
+  std::vector<BnDesc> layers;
+  layers.reserve((size_t)n_layers);
+  for (int32_t i = 0; i < n_layers; ++i) {
+    const squant_bn_t& l = h_layers[i];
+    if (!l.gamma || !l.beta) return SQUANT_ERR_NULL;
+    if (l.channels <= 0) return SQUANT_ERR_SHAPE;
+    layers.push_back(BnDesc{l.gamma, l.beta, l.channels, l.relu, i, 0});
+  }
+  if (!d_workspace || workspace_bytes < squant_activation_workspace_bytes(n_layers) ||
+      (reinterpret_cast<uintptr_t>(d_workspace) & 15u) != 0)
+    return SQUANT_ERR_WORKSPACE;
+  return launch_activation_ranges(layers, n_sigma, bits, d_ranges, static_cast<BnDesc*>(d_workspace),
+                                  (hipStream_t)stream);
+}
+
+size_t squant_network_workspace_bytes(int32_t n_layers) {
+  if (n_layers <= 0) return 0;
+  const size_t w = (squant_batched_workspace_bytes(n_layers) + 15) / 16 * 16;
+  return w + squant_activation_workspace_bytes(n_layers);
+}
+
+int squant_quantize_network(const squant_layer_t* h_layers, int32_t n_layers, int32_t weight_bits,
+                            squant_mode_t mode, int32_t act_bits, float n_sigma,
+                            squant_act_range_t* d_ranges, void* d_workspace,
+                            size_t workspace_bytes, void* stream) {
+  if (n_layers < 0) return SQUANT_ERR_SHAPE;
+  if (n_layers == 0) return SQUANT_OK;
+  if (!h_layers) return SQUANT_ERR_NULL;
+  if (int rc = check_activation_args(act_bits, n_sigma)) return rc;
+  std::vector<squant_tensor_t> weights((size_t)n_layers);
+  std::vector<BnDesc> bns;
+  for (int32_t i = 0; i < n_layers; ++i) {
+    weights[(size_t)i] = h_layers[i].weight;
+    const squant_bn_t& l = h_layers[i].bn;
+    if (!l.gamma) continue;
+    if (!l.beta || !d_ranges) return SQUANT_ERR_NULL;
+    if (l.channels <= 0) return SQUANT_ERR_SHAPE;
+    bns.push_back(BnDesc{l.gamma, l.beta, l.channels, l.relu, i, 0});
+  }
+  if (!d_workspace || workspace_bytes < squant_network_workspace_bytes(n_layers) ||
+      (reinterpret_cast<uintptr_t>(d_workspace) & 15u) != 0)
+    return SQUANT_ERR_WORKSPACE;
+  const size_t w_bytes = (squant_batched_workspace_bytes(n_layers) + 15) / 16 * 16;
+  if (int rc = squant_quantize_batched(weights.data(), n_layers, weight_bits, mode, d_workspace, w_bytes,
+                                       stream))
+    return rc;
+  if (bns.empty()) return SQUANT_OK;
+  return launch_activation_ranges(bns, n_sigma, act_bits, d_ranges,
+                                  reinterpret_cast<BnDesc*>(static_cast<char*>(d_workspace) + w_bytes),
+                                  (hipStream_t)stream);
+}
+
 int64_t squant_max_channel_elems(int32_t kh, int32_t kw) {
   if (kh <= 0 || kw <= 0) return 0;
   const DeviceLimits lim = device_limits();
@@ -439,6 +536,6 @@ const char* squant_status_string(int status) {
   }
 }
 
-int squant_version(void) { return 120; }
+int squant_version(void) { return 121; }
 
 }  // extern "C"
