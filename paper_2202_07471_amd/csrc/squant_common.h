@@ -151,30 +151,8 @@ __device__ __forceinline__ uint32_t wave_prefix_max_u32(uint32_t x) {
 }
 
 // Workgroup-wide versions: every thread returns the result.  `slot` holds >= 16 entries.
-__device__ __forceinline__ float block_max_dpp(float v, float* slot) {
-  v = wave_max_dpp(v);
-  const int wid = threadIdx.x / kWave, nw = (blockDim.x + kWave - 1) / kWave;
-  __syncthreads();
-  if ((threadIdx.x & (kWave - 1)) == 0) slot[wid] = v;
-  __syncthreads();
-  float r = slot[0];
-  for (int i = 1; i < nw; ++i) r = fmaxf(r, slot[i]);
-  return r;
-}
-
-__device__ __forceinline__ int64_t block_sum_dpp(int32_t v, int64_t* slot) {
-  const int64_t w = wave_sum_dpp(v);
-  const int wid = threadIdx.x / kWave, nw = (blockDim.x + kWave - 1) / kWave;
-  __syncthreads();
-  if ((threadIdx.x & (kWave - 1)) == 0) slot[wid] = w;
-  __syncthreads();
-  int64_t r = slot[0];
-  for (int i = 1; i < nw; ++i) r += slot[i];
-  return r;
-}
-
-// One-barrier versions for callers that pass at least one other workgroup barrier before
-// they reduce into the same slots again (so no wave can still be reading them).
+// One barrier each: for callers that pass at least one other workgroup barrier before they
+// reduce into the same slots again (so no wave can still be reading them).
 __device__ __forceinline__ float block_max_dpp1(float v, float* slot) {
   v = wave_max_dpp(v);
   const int wid = threadIdx.x / kWave, nw = (blockDim.x + kWave - 1) / kWave;

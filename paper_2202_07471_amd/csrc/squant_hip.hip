@@ -1,11 +1,13 @@
 // SQuant weight-quantization solver, gfx950 (MI355X) kernels and C ABI.
 //
 // One workgroup owns one output channel from the first byte read to the last
-// byte written: the channel (cin*kh*kw floats) is read from HBM exactly once
-// into LDS, the absmax scale, rounding (SQuant-E), kernel-wise flip (SQuant-K),
-// candidate update (Algorithm 3) and channel-wise flip (SQuant-C) all run on
-// chip, and only int8 codes and one float scale go back to HBM.  Perturbations
-// are Q23 integers, so every sum is order independent.
+// byte written: the channel's weights are read from HBM once (into registers
+// for 3x3 and 1x1 kernels, into LDS otherwise), the absmax scale, rounding
+// (SQuant-E), kernel-wise flip (SQuant-K), candidate update (Algorithm 3) and
+// channel-wise flip (SQuant-C) all run on chip, and only the codes and one
+// float scale go back to HBM.  Perturbations are Q23 integers, so every sum is
+// order independent.  This file is the host side: argument checks, the choice
+// of kernel variant per tensor, the grouping of a batch into launches.
 //
 // Section / algorithm numbers refer to "SQuant: On-the-Fly Data-Free
 // Quantization via Diagonal Hessian Approximation" (ICLR 2022).
