@@ -14,6 +14,7 @@ namespace squant {
 constexpr int32_t kOne = 1 << 23;   // 1.0 in Q23
 constexpr int32_t kHalf = 1 << 22;  // 0.5 in Q23
 constexpr int kWave = 64;
+constexpr int kXcdRun = 64;  // consecutive channels one XCD takes at a time (see locate)
 
 struct TensorDesc {
   const void* w;  // weights, in the launch's weight type
@@ -40,6 +41,18 @@ struct LaunchArgs {
 // ---------------------------------------------------------------------------
 
 __device__ __forceinline__ TensorDesc locate(const LaunchArgs& a, int g, int& m) {
+  // Workgroups are dealt to the 8 XCDs round robin.  Re-deal them so that every XCD works on
+  // runs of kXcdRun consecutive channels (consecutive memory): within each group of
+  // 8 * kXcdRun workgroups, XCD x takes channels x * kXcdRun .. x * kXcdRun + kXcdRun - 1.
+  // The tail that does not fill a group keeps its order.  Measured 1 % faster on the large
+  // 3x3 workload with runs of 64 to 256, neutral elsewhere; whole eighths gain nothing.
+  {
+    constexpr int group = 8 * kXcdRun;
+    if (g < a.total - a.total % group) {
+      const int r = g % group;
+      g = g - r + (r & 7) * kXcdRun + (r >> 3);
+    }
+  }
   if (a.table == nullptr) {
     m = g;
     return a.single;
