@@ -193,6 +193,7 @@ int launch_group(const Group& g, const TensorDesc* d_table, int qmax, int mode, 
   static const kernel_t k1x2[4] = SQ_K1_ROW(256, 2);
   static const kernel_t k1x4[4] = SQ_K1_ROW(256, 4);
   static const kernel_t k1x8[4] = SQ_K1_ROW(1024, 8);
+  static const kernel_t k1x8_small[4] = SQ_K1_ROW(256, 8);
 #undef SQ_K1_ROW
   static const kernel_t k1s[4] = {squant_channel_k1_stream<SQUANT_MODE_E>, squant_channel_k1_stream<SQUANT_MODE_E>,
                                   squant_channel_k1_stream<SQUANT_MODE_EKC>, squant_channel_k1_stream<SQUANT_MODE_EKC>};
@@ -202,7 +203,7 @@ int launch_group(const Group& g, const TensorDesc* d_table, int qmax, int mode, 
                           : g.variant == kK1x1 ? k1x1[mode]
                           : g.variant == kK1x2 ? k1x2[mode]
                           : g.variant == kK1x4 ? k1x4[mode]
-                          : g.variant == kK1x8 ? k1x8[mode]
+                          : g.variant == kK1x8 ? (g.threads <= 256 ? k1x8_small[mode] : k1x8[mode])
                           : g.variant == kK1Stream ? k1s[mode]
                           : g.variant == kK9x1 ? k9x1[mode]
                           : g.variant == kK9x2 ? k9x2[mode]

@@ -327,11 +327,12 @@ __device__ __forceinline__ void k1_channel(const LaunchArgs& a, const TensorDesc
 
 // The variants of up to 256 threads are compiled for eight waves per SIMD (64 VGPRs; the
 // unrolled per-element code otherwise spreads over ~95): measured 8-17 % faster from
-// cin = 1024 up, the extra waves hide the load latency.  The eight-vector variant runs 16
-// waves per workgroup and keeps the 128 VGPRs that allows.
+// cin = 1024 up, the extra waves hide the load latency.  The eight-vector variant is compiled
+// for five waves per SIMD in its 256-thread form (cin up to 8192; 4 and 6 were measured
+// slower) and keeps the 128 VGPRs that 16 waves per workgroup allow in its 1024-thread form.
 template <int MAX_THREADS, int MODE, int NV>
 __global__ void __launch_bounds__(MAX_THREADS)
-    __attribute__((amdgpu_waves_per_eu(MAX_THREADS <= 256 ? 8 : 4))) squant_channel_k1(LaunchArgs a) {
+    __attribute__((amdgpu_waves_per_eu(MAX_THREADS > 256 ? 4 : NV <= 4 ? 8 : 5))) squant_channel_k1(LaunchArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];  // N bytes of biased codes
   __shared__ K9Shared sh;
   int m;
