@@ -21,15 +21,15 @@ struct TensorDesc {
   void* out;      // codes or dequantised weights, in the launch's output format
   float* scales;
   int32_t M, N, K;
-  int32_t first;  // index of this tensor's channel 0 within its launch
+  int32_t first;  // this tensor's first workgroup within its launch
 };
 
 struct LaunchArgs {
   TensorDesc single;        // used when table == nullptr
   const TensorDesc* table;  // device table, n_tensors entries ordered by `first`
   int32_t n_tensors;
-  int32_t total;            // output channels in this launch
-  int32_t uniform_m;        // > 0: every tensor of the table has this many channels
+  int32_t total;            // workgroups in this launch (one per output channel, except depthwise)
+  int32_t uniform_m;        // > 0: every tensor of the table takes this many workgroups
   int32_t qmax;
   int32_t mode;
   int32_t out_format;       // squant_output_t

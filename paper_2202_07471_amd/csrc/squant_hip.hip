@@ -136,6 +136,7 @@ Plan plan_tensor(const void* w, const void* out, int64_t N, int64_t K, int lds_l
       const int nv = variant == kK1x1 ? 1 : variant == kK1x2 ? 2 : variant == kK1x4 ? 4 : 8;
       return Plan{variant, (int)round_up64((N / 4 + nv - 1) / nv), round_up((size_t)N, 16)};
     }
+    case kDw9: return Plan{kDw9, kWave, 16};  // no LDS; 16 stands for "fits"
     case kK1Stream: {
       const size_t lds = round_up((size_t)N, 16);  // the channel's int8 codes
       if (lds + sizeof(K9Shared) + 64 > (size_t)lds_limit) return Plan{kK1Stream, 0, 0};
@@ -160,7 +161,12 @@ int launch_group(const Group& g, const TensorDesc* d_table, int qmax, int mode, 
   LaunchArgs a{};
   int64_t total = 0;
   bool uniform = true;
-  for (const auto& t : g.t) { total += t.M; uniform &= (t.M == g.t[0].M); }
+  const int64_t items0 = work_items(g.t[0].M, g.t[0].N, g.t[0].K, g.threads);
+  for (const auto& t : g.t) {
+    const int64_t items = work_items(t.M, t.N, t.K, g.threads);
+    total += items;
+    uniform &= items == items0;
+  }
   if (total <= 0 || total > 0x7fffffff) return SQUANT_ERR_SHAPE;
   if (d_table == nullptr) {
     a.single = g.t[0];
@@ -171,7 +177,7 @@ int launch_group(const Group& g, const TensorDesc* d_table, int qmax, int mode, 
     a.n_tensors = (int)g.t.size();
   }
   a.total = (int32_t)total;
-  a.uniform_m = uniform ? g.t[0].M : 0;
+  a.uniform_m = uniform ? (int32_t)items0 : 0;
   a.qmax = qmax;
   a.mode = mode;
   a.out_format = output;
@@ -197,6 +203,8 @@ int launch_group(const Group& g, const TensorDesc* d_table, int qmax, int mode, 
 #undef SQ_K1_ROW
   static const kernel_t k1s[4] = {squant_channel_k1_stream<SQUANT_MODE_E>, squant_channel_k1_stream<SQUANT_MODE_E>,
                                   squant_channel_k1_stream<SQUANT_MODE_EKC>, squant_channel_k1_stream<SQUANT_MODE_EKC>};
+  static const kernel_t dw9[4] = {squant_channel_dw9<SQUANT_MODE_E>, squant_channel_dw9<SQUANT_MODE_EK>,
+                                  squant_channel_dw9<SQUANT_MODE_EKC>, squant_channel_dw9<SQUANT_MODE_EC>};
   static const kernel_t mixed[4] = {squant_channel_mixed<SQUANT_MODE_E>, squant_channel_mixed<SQUANT_MODE_EK>,
                                     squant_channel_mixed<SQUANT_MODE_EKC>, squant_channel_mixed<SQUANT_MODE_EC>};
   const kernel_t kernel = (g.variant == kMixed || g.variant == kMixedWave) ? mixed[mode]
@@ -205,6 +213,7 @@ int launch_group(const Group& g, const TensorDesc* d_table, int qmax, int mode, 
                           : g.variant == kK1x4 ? k1x4[mode]
                           : g.variant == kK1x8 ? (g.threads <= 256 ? k1x8_small[mode] : k1x8[mode])
                           : g.variant == kK1Stream ? k1s[mode]
+                          : g.variant == kDw9 ? dw9[mode]
                           : g.variant == kK9x1 ? k9x1[mode]
                           : g.variant == kK9x2 ? k9x2[mode]
                           : g.variant == kK9x4 ? (g.threads <= 256 ? k9x4[mode] : k9x4_large[mode])
@@ -354,11 +363,16 @@ int squant_quantize_batched_ex(const squant_tensor_t* h_tensors, int32_t n_tenso
       g = &groups.back();
     }
     if (in_mixed) { g->threads = std::max(g->threads, p.threads); g->lds = std::max(g->lds, p.lds); }
+    g->t.push_back(TensorDesc{t.w, t.codes, t.scales, t.cout, t.cin, (int32_t)((int64_t)t.kh * t.kw), 0});
+  }
+  // first workgroup of every tensor within its launch, now that the launch shapes are final
+  for (auto& g : groups) {
     int64_t first = 0;
-    if (!g->t.empty()) first = (int64_t)g->t.back().first + g->t.back().M;
-    if (first + t.cout > 0x7fffffff) return SQUANT_ERR_SHAPE;
-    g->t.push_back(TensorDesc{t.w, t.codes, t.scales, t.cout, t.cin, (int32_t)((int64_t)t.kh * t.kw),
-                              (int32_t)first});
+    for (auto& t : g.t) {
+      t.first = (int32_t)first;
+      first += work_items(t.M, t.N, t.K, g.threads);
+      if (first > 0x7fffffff) return SQUANT_ERR_SHAPE;
+    }
   }
 
   hipStream_t st = (hipStream_t)stream;
@@ -539,6 +553,6 @@ const char* squant_status_string(int status) {
   }
 }
 
-int squant_version(void) { return 121; }
+int squant_version(void) { return 122; }
 
 }  // extern "C"

@@ -264,4 +264,79 @@ __global__ void __launch_bounds__(MAX_THREADS) squant_channel_k9(LaunchArgs a) {
   k9_channel<MODE, KPT>(a, d, m, smem, sh);
 }
 
+// ---------------------------------------------------------------------------
+// Depthwise 3x3 convolutions (cin per group = 1): an output channel is a single 3x3 kernel,
+// so one thread takes a whole channel - its own absmax scale, SQuant-E and SQuant-K in
+// registers through k9_solve.  SQuant-C on a one-kernel channel: after SQuant-K the
+// channel's sum is the kernel's, at most 0.5, so nothing flips (E&K&C equals E&K); without
+// SQuant-K (mode E&C) the kernel's one candidate flips when the sum rounds to 1 or more.
+// `item` is the workgroup's index within the tensor: thread t has channel item * T + t.
+// No workgroup-wide step, no LDS.
+// ---------------------------------------------------------------------------
+template <int MODE>
+__device__ __forceinline__ void dw9_channels(const LaunchArgs& a, const TensorDesc& d, int item) {
+  constexpr int KM = MODE == SQUANT_MODE_EKC ? SQUANT_MODE_EK : MODE;
+  const int c = item * (int)blockDim.x + (int)threadIdx.x;
+  if (c >= d.M) return;
+  const float qmaxf = (float)a.qmax;
+  float w[9];
+  if (a.wtype == SQUANT_W_F32) {
+    k9_load_kernel(w, 0, static_cast<const float*>(d.w), 9u * (uint32_t)c);
+  } else {
+#pragma unroll
+    for (int i = 0; i < 9; ++i) w[i] = load_weight(d.w, 9 * (size_t)c + i, a.wtype);
+  }
+  float amax = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 9; ++i) amax = fmaxf(amax, fabsf(w[i]));
+  const float s = amax > 0.0f ? amax / qmaxf : 1.0f;
+  d.scales[c] = s;
+
+  float cf[9];
+  int32_t esum = 0;
+  uint32_t cw = kNoCandidate, zero = 0;
+  int ci = 0;
+  k9_solve<9, false, KM>(w, 0, s, 0.0f, qmaxf, cf, esum, cw, ci, zero);
+  if (MODE == SQUANT_MODE_EC) {
+    const int32_t mag = esum < 0 ? -esum : esum;
+    if (flips_for(mag) >= 1 && cw != kNoCandidate) {
+      const float step = esum > 0 ? -1.0f : 1.0f;  // one step against the sum
+#pragma unroll
+      for (int i = 0; i < 9; ++i) cf[i] += (i == ci) ? step : 0.0f;
+    }
+  }
+
+  int code[9];
+#pragma unroll
+  for (int i = 0; i < 9; ++i) code[i] = (int)cf[i] - 128;
+  if (a.out_format == SQUANT_OUT_INT8) {
+    int8_t* out = static_cast<int8_t*>(d.out) + 9 * (size_t)c;
+#pragma unroll
+    for (int i = 0; i < 9; ++i) out[i] = (int8_t)code[i];
+  } else if (a.out_format == SQUANT_OUT_INT4) {
+    uint8_t* out = static_cast<uint8_t*>(d.out) + 5 * (size_t)c;  // rows of (9 + 1) / 2 bytes
+#pragma unroll
+    for (int j = 0; j < 5; ++j) {
+      const uint32_t lo = (uint32_t)code[2 * j] & 0xFu;
+      const uint32_t hi = j < 4 ? ((uint32_t)code[2 * j + 1] & 0xFu) : 0u;
+      out[j] = (uint8_t)(lo | (hi << 4));
+    }
+  } else if (a.out_format == SQUANT_OUT_BF16) {
+    uint16_t* out = static_cast<uint16_t*>(d.out) + 9 * (size_t)c;
+#pragma unroll
+    for (int i = 0; i < 9; ++i) out[i] = (uint16_t)bf16_bits((float)code[i] * s);
+  } else {  // SQUANT_OUT_F32
+    float* out = static_cast<float*>(d.out) + 9 * (size_t)c;
+#pragma unroll
+    for (int i = 0; i < 9; ++i) out[i] = (float)code[i] * s;
+  }
+}
+
+template <int MODE>
+__global__ void __launch_bounds__(256) squant_channel_dw9(LaunchArgs a) {
+  int m;
+  const TensorDesc d = locate(a, blockIdx.x, m);
+  dw9_channels<MODE>(a, d, m);
+}
+
 }  // namespace squant

@@ -38,6 +38,8 @@ __global__ void __launch_bounds__(kMixedMaxThreads) squant_channel_mixed(LaunchA
     if (nvec <= T) k1_channel<M1, 1>(a, d, m, smem, sh);
     else if (nvec <= 2 * T) k1_channel<M1, 2>(a, d, m, smem, sh);
     else k1_channel<M1, 4>(a, d, m, smem, sh);
+  } else if (family == 3) {
+    dw9_channels<MODE>(a, d, m);
   } else {
     generic_channel(a, d, m, smem, gs);
   }

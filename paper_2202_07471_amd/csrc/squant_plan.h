@@ -13,7 +13,8 @@ enum Variant {
   kGeneric = 0,
   kK9x1 = 1, kK9x2 = 2, kK9x4 = 3,             // 3x3 kernels per thread: 1, 2, 4
   kK1x1 = 4, kK1x2 = 5, kK1x4 = 6, kK1x8 = 7,  // 1x1 / FC: 16-byte vectors per thread: 1, 2, 4, 8
-  kK1Stream = 8                                // 1x1 / FC beyond kMaxK1Cin: weights walked repeatedly
+  kK1Stream = 8,                               // 1x1 / FC beyond kMaxK1Cin: weights walked repeatedly
+  kDw9 = 9                                     // depthwise 3x3 (cin per group = 1): one thread per channel
 };
 
 constexpr int kMaxK9Cin = 4096;   // 3x3 variant: cin % 4 == 0 up to here
@@ -22,9 +23,10 @@ constexpr int kMaxK1Cin = 32768;  // 1x1 variant: cin % 4 == 0 up to here
 SQ_HD int64_t round_up64(int64_t v) { return (v + 63) / 64 * 64; }
 
 // Kernel family of a tensor: 9 = the 3x3 kernel, 1 = the 1x1 / FC kernel, 2 = the streaming
-// 1x1 / FC kernel, 0 = generic.
+// 1x1 / FC kernel, 3 = depthwise 3x3, 0 = generic.
 // aligned: weights on 16 bytes and output on 4 (what the vector loads / stores need)
 SQ_HD int choose_family(int64_t N, int64_t K, bool aligned) {
+  if (K == 9 && N == 1) return 3;  // any alignment: element-wise loads and stores
   if (K == 9 && (N & 3) == 0 && N <= kMaxK9Cin && aligned) return 9;
   if (K == 1 && (N & 3) == 0 && N <= kMaxK1Cin && aligned) return 1;
   if (K == 1 && (N & 3) == 0 && aligned) return 2;
@@ -56,7 +58,14 @@ SQ_HD int choose_variant(int64_t N, int64_t K, bool aligned) {
     return nvec <= 64 ? kK1x1 : nvec <= 128 ? kK1x2 : nvec <= 1024 ? kK1x4 : kK1x8;
   }
   if (family == 2) return kK1Stream;
+  if (family == 3) return kDw9;
   return kGeneric;
+}
+
+// Workgroups a tensor of M output channels takes in a launch of T threads per workgroup:
+// one per channel, except depthwise 3x3 where every thread has a channel of its own.
+SQ_HD int64_t work_items(int64_t M, int64_t N, int64_t K, int64_t T) {
+  return (K == 9 && N == 1) ? (M + T - 1) / T : M;
 }
 
 SQ_HD bool pointers_aligned(const void* w, const void* out) {

@@ -38,12 +38,15 @@ int main() {
           const int64_t nvec = N / 4, threads = round_up64((nvec + nv - 1) / nv);
           bad += threads * nv < nvec;
           bad += threads > (nv == 8 ? 1024 : 256);
+        } else if (family == 3) {
+          bad += v != kDw9 || K != 9 || N != 1;
+          bad += work_items(130, N, K, 64) != 3 || work_items(128, N, K, 64) != 2;
         } else if (family == 2) {
           ++stream;  // a 1x1 channel too long for the register-resident kernel
           bad += v != kK1Stream || K != 1 || !aligned || N % 4 || N <= kMaxK1Cin;
         } else {
           ++generic;
-          bad += v != kGeneric;
+          bad += v != kGeneric || work_items(130, N, K, 64) != 130;
           bad += aligned && K == 9 && N % 4 == 0 && N <= kMaxK9Cin;
           bad += aligned && K == 1 && N % 4 == 0;
         }

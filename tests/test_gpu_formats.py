@@ -65,7 +65,7 @@ SHAPES = [
     (6, 64, 3, 3), (6, 128, 3, 3), (4, 512, 3, 3), (5, 4, 3, 3), (5, 12, 3, 3), (3, 36, 3, 3),
     (9, 512, 1, 1), (7, 1028, 1, 1), (40, 16, 1, 1), (3, 8192, 1, 1), (5, 2048, 1, 1),
     (33, 17, 3, 3), (96, 1, 3, 3), (8, 5, 3, 3), (5, 3, 7, 7), (7, 2, 5, 5), (4, 3, 11, 11),
-    (10, 1, 1, 1), (17, 63, 1, 1), (1, 1, 1, 1),
+    (10, 1, 1, 1), (17, 63, 1, 1), (1, 1, 1, 1), (200, 1, 3, 3), (1, 1, 3, 3),
 ]
 
 

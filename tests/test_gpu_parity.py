@@ -235,6 +235,19 @@ def test_config5_full_size_sampled(sq):
         assert bool((scales[t] > 0).all())
 
 
+@pytest.mark.parametrize("kind", ["normal", "heavy", "grid"])
+@pytest.mark.parametrize("cout", [1, 63, 64, 65, 960, 4097])
+def test_depthwise_3x3_thread_per_channel(sq, cout, kind):
+    """Depthwise 3x3 layers: every thread solves a whole output channel."""
+    w = rand_weights((cout, 1, 3, 3), 600 + cout, kind)
+    if cout > 2:
+        w[1] = 0.0
+        w[2] = -0.7                      # one-sided: the E&C candidate must flip
+    for bits, mode in ((4, 2), (4, 3), (8, 1), (2, 3), (3, 0)):
+        codes, scales = run_single(sq, w, bits, mode)
+        assert_same(codes, scales, w, bits, mode, what=f"depthwise cout={cout} {kind} bits={bits} mode={mode}")
+
+
 @pytest.mark.parametrize("shape", [(3, 492, 3, 3), (2, 512, 3, 3), (2, 8192, 1, 1), (2, 32768, 1, 1), (3, 64, 3, 3)])
 def test_one_sided_perturbations_have_huge_channel_sums(sq, shape):
     """Every element rounds the same way, so the channel sum reaches thousands of steps: the

@@ -57,7 +57,7 @@ SHAPES = [
     (6, 96, 3, 3), (2, 4096, 3, 3), (4, 1100, 3, 3),
     (9, 512, 1, 1), (7, 1028, 1, 1), (40, 16, 1, 1), (3, 8192, 1, 1), (2, 32764, 1, 1),
     (33, 17, 3, 3), (96, 1, 3, 3), (8, 5, 3, 3), (5, 3, 7, 7), (4, 3, 11, 11), (17, 63, 1, 1),
-    (1, 1, 1, 1),
+    (1, 1, 1, 1), (130, 1, 3, 3),
 ]
 
 
