@@ -9,7 +9,8 @@ namespace squant {
 // tuning switches (compile time)
 #ifndef SQ_OPT_NT_LOAD
 #define SQ_OPT_NT_LOAD 0   // off: the three 12-byte loads of a kernel share cache lines, and
-                           // non-temporal loads were measured 6% slower
+                           // non-temporal loads were measured 6-20% slower (the hint on the
+                           // second and third load only changes nothing)
 #endif
 #ifndef SQ_OPT_NT_STORE
 #define SQ_OPT_NT_STORE 1  // codes are written once: non-temporal stores (measured 1% faster)
