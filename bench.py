@@ -37,12 +37,14 @@ K9_SOURCES = ("squant_k9.h", "squant_select.h", "squant_io.h", "squant_common.h"
 
 
 def kernel_source_digest() -> str:
-    """SHA-256 over the sources the 3x3 kernel is compiled from."""
+    """SHA-256 over the code (comments and blank space dropped) the 3x3 kernel is compiled from."""
     import hashlib
+    import re
     h = hashlib.sha256()
     for name in K9_SOURCES:
-        with open(os.path.join(ROOT, "paper_2202_07471_amd", "csrc", name), "rb") as f:
-            h.update(f.read())
+        with open(os.path.join(ROOT, "paper_2202_07471_amd", "csrc", name)) as f:
+            text = re.sub(r"//[^\n]*", "", f.read())
+        h.update(" ".join(text.split()).encode())
     return h.hexdigest()
 
 
