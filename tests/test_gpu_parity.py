@@ -189,6 +189,37 @@ def test_mixed_launch_with_every_variant_and_large_members(sq):
             assert_same(c, sc, w, bits, mode, what=f"mixed launch {sh} bits={bits} mode={mode}")
 
 
+def test_many_tensors_in_one_call(sq):
+    """700 small tensors of assorted shapes: the descriptor table goes up in several pieces."""
+    rng = np.random.default_rng(8)
+    pool = [(8, 16, 3, 3), (4, 64, 1, 1), (16, 1, 3, 3), (3, 5, 5, 5), (2, 128, 3, 3), (5, 33, 1, 1), (1, 2048, 1, 1)]
+    shapes = [pool[int(rng.integers(0, len(pool)))] for _ in range(700)]
+    ws = [(rng.standard_normal(sh) * 0.05).astype(np.float32) for sh in shapes]
+    codes, scales = run_batched(sq, ws, 4, 2)
+    for i, (w, c, sc) in enumerate(zip(ws, codes, scales)):
+        assert_same(c, sc, w, 4, 2, threads=1, what=f"tensor {i} {w.shape}")
+
+
+def test_caller_stream_is_honoured(sq):
+    """Work goes to the stream handed in: queued behind a long copy on that stream, the result is
+    complete once that stream is synchronised, and two streams do not disturb each other."""
+    w1 = rand_weights((64, 256, 3, 3), 31, "normal")
+    w2 = rand_weights((48, 1024, 1, 1), 32, "heavy")
+    d1, d2 = torch.from_numpy(w1).cuda(), torch.from_numpy(w2).cuda()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    big = torch.empty(1 << 26, device="cuda")
+    with torch.cuda.stream(s1):
+        big.normal_()                                   # keeps s1 busy first
+        c1, sc1 = sq.squant_quantize(d1, 4, 2, stream=s1)
+    with torch.cuda.stream(s2):
+        c2, sc2 = sq.squant_quantize(d2, 8, 2, stream=s2)
+    s1.synchronize()
+    s2.synchronize()
+    assert_same(c1, sc1, w1, 4, 2, what="stream 1")
+    assert_same(c2, sc2, w2, 8, 2, what="stream 2")
+
+
 def test_config5_slice_batched(sq):
     specs = synth.config_specs(5, n_tensors=6)
     ws = [synth.generate(s) for s in specs]
