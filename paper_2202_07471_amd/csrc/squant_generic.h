@@ -151,14 +151,30 @@ __device__ int64_t kernel_stage_wave(int32_t* pk, int8_t* ck, int K, int mode, i
   uint32_t T = 0xFFFFFFFFu;  // key of the k-th largest same-sign element (nothing flips if k = 0)
   uint32_t take_eq = 0;      // how many of the elements with key == T flip
   if (k > 0) {
+    // kernels of up to 256 elements keep their keys in registers for the 23 steps (a 7x7
+    // kernel: one register per lane) instead of reading LDS in every step
+    constexpr int kRegChunks = 4;
+    const bool in_regs = K <= kRegChunks * kWave;
+    uint32_t kreg[kRegChunks];
+#pragma unroll
+    for (int r = 0; r < kRegChunks; ++r) {
+      const int i = r * kWave + lane;
+      kreg[r] = (in_regs && i < K) ? same_sign_key(pk[i], sgn) : 0u;
+    }
     uint32_t prefix = 0, need = k;
     for (int b = 22; b >= 0; --b) {
       const uint32_t want = (prefix << 1) | 1u;
       uint32_t cnt = 0;
-      for (int base = 0; base < K; base += kWave) {
-        const int i = base + lane;
-        const uint32_t key = i < K ? same_sign_key(pk[i], sgn) : 0u;
-        cnt += (uint32_t)__popcll(__ballot(key != 0 && (key >> b) == want));
+      if (in_regs) {
+#pragma unroll
+        for (int r = 0; r < kRegChunks; ++r)
+          if (r * kWave < K) cnt += (uint32_t)__popcll(__ballot(kreg[r] != 0 && (kreg[r] >> b) == want));
+      } else {
+        for (int base = 0; base < K; base += kWave) {
+          const int i = base + lane;
+          const uint32_t key = i < K ? same_sign_key(pk[i], sgn) : 0u;
+          cnt += (uint32_t)__popcll(__ballot(key != 0 && (key >> b) == want));
+        }
       }
       if (cnt >= need) prefix = want; else { need -= cnt; prefix <<= 1; }
     }
@@ -347,8 +363,25 @@ __device__ __forceinline__ void generic_channel(const LaunchArgs& a, const Tenso
       const int64_t kc = flips_for(ec < 0 ? -ec : ec);
       if (kc > 0) {
         const uint32_t need = (uint32_t)(kc > (int64_t)N ? (int64_t)N : kc);
-        const SelectResult r = radix_select(cand, N, sgn, need, hist, bcast);
-        apply_channel_flips(cand, cidx, code, N, K, sgn, r);
+        if (N <= kWave) {
+          // few kernels (a 7x7 stem has three): lane n of the first wave holds candidate n and
+          // ranks it against the others directly, larger |v| first, then lower kernel index
+          if (tid < kWave) {
+            const uint32_t key = tid < N ? cand_key(cand[tid], sgn) : 0u;
+            uint32_t rank = 0;
+            for (int o = 0; o < N; ++o) {
+              const uint32_t ko = (uint32_t)__builtin_amdgcn_readlane((int)key, o);
+              rank += (ko > key || (ko == key && o < tid)) ? 1u : 0u;
+            }
+            if (key != 0 && rank < need) {
+              const int j = tid * K + (cidx ? cidx[tid] : 0);
+              code[j] = (int8_t)(code[j] - sgn);
+            }
+          }
+        } else {
+          const SelectResult r = radix_select(cand, N, sgn, need, hist, bcast);
+          apply_channel_flips(cand, cidx, code, N, K, sgn, r);
+        }
       }
     }
   }

@@ -117,6 +117,7 @@ struct Group {
   int threads;
   size_t lds;
   std::vector<TensorDesc> t;
+  bool fixed_threads = false;  // mixed launch: a non-generic member has set the workgroup size
 };
 
 struct Plan { int variant; int threads; size_t lds; };
@@ -362,7 +363,18 @@ int squant_quantize_batched_ex(const squant_tensor_t* h_tensors, int32_t n_tenso
       groups.push_back(Group{in_mixed ? mixed_kind : p.variant, p.threads, p.lds, {}});
       g = &groups.back();
     }
-    if (in_mixed) { g->threads = std::max(g->threads, p.threads); g->lds = std::max(g->lds, p.lds); }
+    if (in_mixed) {
+      // the workgroup size follows the specialised routines (their kernels / vectors per thread
+      // depend on it); the generic routine strides by whatever size it is given, so a generic
+      // member only sets the size of a launch that has no other kind of member
+      if (p.variant != kGeneric) {
+        g->threads = g->fixed_threads ? std::max(g->threads, p.threads) : p.threads;
+        g->fixed_threads = true;
+      } else if (!g->fixed_threads) {
+        g->threads = std::max(g->threads, p.threads);
+      }
+      g->lds = std::max(g->lds, p.lds);
+    }
     g->t.push_back(TensorDesc{t.w, t.codes, t.scales, t.cout, t.cin, (int32_t)((int64_t)t.kh * t.kw), 0});
   }
   // first workgroup of every tensor within its launch, now that the launch shapes are final
