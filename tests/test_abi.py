@@ -159,3 +159,14 @@ def test_activation_and_network_argument_checks(L):
     assert g(layers, 1, 9, 2, 8, 6.0, out, ws, 4096, None) == 3
     assert g(layers, 1, 4, 7, 8, 6.0, out, ws, 4096, None) == 4
     assert g(layers, 1, 4, 2, 8, 6.0, out, ws, 8, None) == 5
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C header: it must compile as C99 on its own."""
+    import subprocess
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "squant.h"\n'
+                   'int probe(void) { squant_tensor_t t; squant_layer_t l; squant_act_range_t r;\n'
+                   '  (void)t; (void)l; (void)r; return (int)SQUANT_OUT_BF16 + (int)SQUANT_W_BF16 + (int)SQUANT_MODE_EC; }\n')
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only",
+                           "-I", os.path.join(ROOT, "include"), str(src)])
