@@ -109,11 +109,13 @@ int squant_quantize(const float* d_w, int32_t cout, int32_t cin, int32_t kh, int
                     int32_t bits, squant_mode_t mode, int8_t* d_codes, float* d_scales,
                     void* stream);
 
-/* Device bytes squant_quantize_batched needs for its descriptor table. */
+/* Device bytes squant_quantize_batched asks for as workspace.  (The present kernels carry
+ * the tensor descriptors in their kernel arguments, up to 256 per launch, and do not touch
+ * the workspace; it stays part of the contract and is validated.) */
 size_t squant_batched_workspace_bytes(int32_t n_tensors);
 
 /* Quantize a set of tensors (the layers of a network are independent, Section 4.2)
- * with one launch per kernel variant present instead of one per tensor.
+ * with a few launches for the whole set instead of one per tensor.
  * h_tensors: HOST array of n_tensors descriptors holding DEVICE pointers; it may be
  * freed or reused as soon as the call returns.  d_workspace: caller-allocated device
  * memory of at least squant_batched_workspace_bytes(n_tensors), 16-byte aligned; it must
@@ -199,8 +201,7 @@ int64_t squant_max_channel_elems(int32_t kh, int32_t kw);
  * squant_kernel_timer_enable(slots) creates `slots` pairs of HIP events (0 releases them
  * and switches the timer off).  While it is on, every squant_quantize /
  * squant_quantize_batched call of this thread records one event on its stream before its
- * first solver kernel and one after its last (the descriptor upload of a batched call
- * lies outside the pair); call number c since the enable uses pair c mod slots.
+ * first solver kernel and one after its last; call number c since the enable uses pair c mod slots.
  * squant_kernel_timer_elapsed_ms(c, h_ms) waits for call c's second event and writes its
  * elapsed milliseconds to the HOST float *h_ms; SQUANT_ERR_SHAPE if call c was never
  * timed or its pair has been reused. */

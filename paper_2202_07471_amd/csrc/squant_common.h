@@ -24,16 +24,19 @@ struct TensorDesc {
   int32_t first;  // this tensor's first workgroup within its launch
 };
 
+// The tensor descriptors of a launch travel inside the kernel arguments (10 KB for 256 of
+// them, read with scalar loads); a batch of more tensors takes several launches.
+constexpr int kInlineDescs = 256;
+
 struct LaunchArgs {
-  TensorDesc single;        // used when table == nullptr
-  const TensorDesc* table;  // device table, n_tensors entries ordered by `first`
-  int32_t n_tensors;
+  int32_t n_tensors;        // descriptors in `table`, ordered by `first`
   int32_t total;            // workgroups in this launch (one per output channel, except depthwise)
   int32_t uniform_m;        // > 0: every tensor of the table takes this many workgroups
   int32_t qmax;
   int32_t mode;
   int32_t out_format;       // squant_output_t
   int32_t wtype;            // squant_wtype_t
+  TensorDesc table[kInlineDescs];
 };
 
 // ---------------------------------------------------------------------------
@@ -53,27 +56,25 @@ __device__ __forceinline__ TensorDesc locate(const LaunchArgs& a, int g, int& m)
       g = g - r + (r & 7) * kXcdRun + (r >> 3);
     }
   }
-  if (a.table == nullptr) {
-    m = g;
-    return a.single;
-  }
-  int t;
-  if (a.uniform_m > 0) {
-    t = g / a.uniform_m;
-  } else {
-    // last t with first[t] <= g.  The offsets ascend, so t + 1 is the number of tensors whose
-    // first channel is <= g: every lane fetches one offset (64 per step, one memory latency
-    // instead of the chain of dependent loads of a binary search) and a ballot counts them.
-    const int lane = threadIdx.x & (kWave - 1);
-    int below = 0;
-    for (int base = 0; base < a.n_tensors; base += kWave) {
-      const int i = base + lane;
-      const int first = i < a.n_tensors ? a.table[i].first : 0x7fffffff;
-      const int cnt = __popcll(__ballot(first <= g));
-      below += cnt;
-      if (cnt < kWave) break;
+  int t = 0;
+  if (a.n_tensors > 1) {
+    if (a.uniform_m > 0) {
+      t = g / a.uniform_m;
+    } else {
+      // last t with first[t] <= g.  The offsets ascend, so t + 1 is the number of tensors whose
+      // first workgroup is <= g: every lane fetches one offset (64 per step, one memory latency
+      // instead of the chain of dependent loads of a binary search) and a ballot counts them.
+      const int lane = threadIdx.x & (kWave - 1);
+      int below = 0;
+      for (int base = 0; base < a.n_tensors; base += kWave) {
+        const int i = base + lane;
+        const int first = i < a.n_tensors ? a.table[i].first : 0x7fffffff;
+        const int cnt = __popcll(__ballot(first <= g));
+        below += cnt;
+        if (cnt < kWave) break;
+      }
+      t = __builtin_amdgcn_readfirstlane(below - 1);
     }
-    t = __builtin_amdgcn_readfirstlane(below - 1);
   }
   const TensorDesc d = a.table[t];
   m = g - d.first;

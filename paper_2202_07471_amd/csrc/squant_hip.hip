@@ -32,14 +32,6 @@ namespace {
 
 using namespace squant;
 
-// Copies a chunk of descriptors passed by value into the device table.
-constexpr int kDescChunk = 256;  // 10 KB of by-value kernel arguments per writer launch
-struct DescChunk { TensorDesc t[kDescChunk]; };
-__global__ void write_table(DescChunk c, int count, TensorDesc* table) {
-  const int i = threadIdx.x;
-  if (i < count) table[i] = c.t[i];
-}
-
 constexpr int kBnChunk = 256;
 struct BnChunk { BnDesc t[kBnChunk]; };
 __global__ void write_bn_table(BnChunk c, int count, BnDesc* table) {
@@ -157,26 +149,24 @@ bool mixable(const Plan& p, size_t lds_cap) {
          p.lds <= lds_cap;
 }
 
-int launch_group(const Group& g, const TensorDesc* d_table, int qmax, int mode, int output,
-                 int wtype, hipStream_t st) {
+// Launches tensors [begin, end) of a group (at most kInlineDescs of them) as one kernel.
+int launch_part(const Group& g, size_t begin, size_t end, int qmax, int mode, int output, int wtype,
+                hipStream_t st) {
   LaunchArgs a{};
   int64_t total = 0;
   bool uniform = true;
-  const int64_t items0 = work_items(g.t[0].M, g.t[0].N, g.t[0].K, g.threads);
-  for (const auto& t : g.t) {
+  const int64_t items0 = work_items(g.t[begin].M, g.t[begin].N, g.t[begin].K, g.threads);
+  for (size_t i = begin; i < end; ++i) {
+    const TensorDesc& t = g.t[i];
     const int64_t items = work_items(t.M, t.N, t.K, g.threads);
+    a.table[i - begin] = t;
+    a.table[i - begin].first = (int32_t)total;  // first workgroup within this launch
     total += items;
     uniform &= items == items0;
+    if (total > 0x7fffffff) return SQUANT_ERR_SHAPE;
   }
-  if (total <= 0 || total > 0x7fffffff) return SQUANT_ERR_SHAPE;
-  if (d_table == nullptr) {
-    a.single = g.t[0];
-    a.table = nullptr;
-    a.n_tensors = 1;
-  } else {
-    a.table = d_table;
-    a.n_tensors = (int)g.t.size();
-  }
+  if (total <= 0) return SQUANT_ERR_SHAPE;
+  a.n_tensors = (int)(end - begin);
   a.total = (int32_t)total;
   a.uniform_m = uniform ? (int32_t)items0 : 0;
   a.qmax = qmax;
@@ -232,6 +222,15 @@ int launch_group(const Group& g, const TensorDesc* d_table, int qmax, int mode, 
   return SQUANT_OK;
 }
 
+// A group goes out in launches of at most kInlineDescs tensors each.
+int launch_group(const Group& g, int qmax, int mode, int output, int wtype, hipStream_t st) {
+  for (size_t begin = 0; begin < g.t.size(); begin += kInlineDescs) {
+    const size_t end = std::min(g.t.size(), begin + (size_t)kInlineDescs);
+    if (int rc = launch_part(g, begin, end, qmax, mode, output, wtype, st)) return rc;
+  }
+  return SQUANT_OK;
+}
+
 void timer_mark(bool start, hipStream_t st) {
   const size_t slots = g_timer.start.size();
   if (slots == 0) return;
@@ -266,8 +265,8 @@ int squant_quantize_ex(const void* d_w, squant_wtype_t wtype, int32_t cout, int3
   Group g{p.variant, p.threads, p.lds, {}};
   g.t.push_back(TensorDesc{d_w, d_out, d_scales, cout, cin, (int32_t)K, 0});
   timer_mark(true, (hipStream_t)stream);
-  const int rc = launch_group(g, nullptr, (1 << (bits - 1)) - 1, (int)mode, (int)output,
-                              (int)wtype, (hipStream_t)stream);
+  const int rc = launch_group(g, (1 << (bits - 1)) - 1, (int)mode, (int)output, (int)wtype,
+                              (hipStream_t)stream);
   timer_mark(false, (hipStream_t)stream);
   return rc;
 }
@@ -377,37 +376,11 @@ int squant_quantize_batched_ex(const squant_tensor_t* h_tensors, int32_t n_tenso
     }
     g->t.push_back(TensorDesc{t.w, t.codes, t.scales, t.cout, t.cin, (int32_t)((int64_t)t.kh * t.kw), 0});
   }
-  // first workgroup of every tensor within its launch, now that the launch shapes are final
-  for (auto& g : groups) {
-    int64_t first = 0;
-    for (auto& t : g.t) {
-      t.first = (int32_t)first;
-      first += work_items(t.M, t.N, t.K, g.threads);
-      if (first > 0x7fffffff) return SQUANT_ERR_SHAPE;
-    }
-  }
-
   hipStream_t st = (hipStream_t)stream;
-  TensorDesc* table = static_cast<TensorDesc*>(d_workspace);
   const int qmax = (1 << (bits - 1)) - 1;
-  // the descriptors of all groups, group after group, go up first (kDescChunk per writer
-  // launch), then the solver kernels follow back to back
-  std::vector<TensorDesc> all;
-  all.reserve((size_t)n_tensors);
-  for (const auto& g : groups) all.insert(all.end(), g.t.begin(), g.t.end());
-  for (size_t c0 = 0; c0 < all.size(); c0 += kDescChunk) {
-    DescChunk chunk{};
-    const int cnt = (int)std::min<size_t>(kDescChunk, all.size() - c0);
-    for (int i = 0; i < cnt; ++i) chunk.t[i] = all[c0 + i];
-    hipLaunchKernelGGL(write_table, dim3(1), dim3(kDescChunk), 0, st, chunk, cnt, table + c0);
-    if (hipGetLastError() != hipSuccess) return SQUANT_ERR_DEVICE;
-  }
   timer_mark(true, st);
-  size_t offset = 0;
-  for (const auto& g : groups) {
-    if (int rc = launch_group(g, table + offset, qmax, (int)mode, (int)output, (int)wtype, st)) return rc;
-    offset += g.t.size();
-  }
+  for (const auto& g : groups)
+    if (int rc = launch_group(g, qmax, (int)mode, (int)output, (int)wtype, st)) return rc;
   timer_mark(false, st);
   return SQUANT_OK;
 }
@@ -565,6 +538,6 @@ const char* squant_status_string(int status) {
   }
 }
 
-int squant_version(void) { return 122; }
+int squant_version(void) { return 123; }
 
 }  // extern "C"
