@@ -162,7 +162,8 @@ typedef struct {
   int32_t zero_point;
 } squant_act_range_t;
 
-/* Device bytes squant_activation_ranges needs for its descriptor table. */
+/* Device bytes squant_activation_ranges asks for as workspace (validated, not touched at
+ * present: the layer descriptors travel in the kernel arguments, 256 per launch). */
 size_t squant_activation_workspace_bytes(int32_t n_layers);
 
 /* h_layers: HOST array of n_layers descriptors holding DEVICE pointers (reusable as soon as

@@ -16,11 +16,21 @@ struct BnDesc {
   int32_t pad_;
 };
 
-__global__ void __launch_bounds__(256) squant_activation_range_kernel(const BnDesc* table, float n_sigma,
-                                                                      int32_t levels_minus_1,
-                                                                      squant_act_range_t* out) {
+// The layer descriptors of a launch travel in the kernel arguments (8 KB for 256 layers).
+constexpr int kInlineBn = 256;
+struct BnArgs {
+  float n_sigma;
+  int32_t levels_minus_1;
+  squant_act_range_t* out;
+  BnDesc layer[kInlineBn];
+};
+
+__global__ void __launch_bounds__(256) squant_activation_range_kernel(BnArgs a) {
   __shared__ float red_lo[16], red_hi[16];
-  const BnDesc d = table[blockIdx.x];
+  const BnDesc d = a.layer[blockIdx.x];
+  const float n_sigma = a.n_sigma;
+  const int32_t levels_minus_1 = a.levels_minus_1;
+  squant_act_range_t* out = a.out;
   float lo = INFINITY, hi = -INFINITY;
   for (int c = threadIdx.x; c < d.channels; c += blockDim.x) {
     const float t = n_sigma * fabsf(d.gamma[c]);

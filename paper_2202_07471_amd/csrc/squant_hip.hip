@@ -32,13 +32,6 @@ namespace {
 
 using namespace squant;
 
-constexpr int kBnChunk = 256;
-struct BnChunk { BnDesc t[kBnChunk]; };
-__global__ void write_bn_table(BnChunk c, int count, BnDesc* table) {
-  const int i = threadIdx.x;
-  if (i < count) table[i] = c.t[i];
-}
-
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
@@ -391,20 +384,20 @@ size_t squant_activation_workspace_bytes(int32_t n_layers) {
 }
 
 namespace {
-// Shared by squant_activation_ranges and squant_quantize_network: `index[i]` is the entry of
-// d_ranges that layers[i] writes.
+// Shared by squant_activation_ranges and squant_quantize_network; every descriptor names the
+// entry of d_ranges it writes.  Launches of at most kInlineBn layers each.
 int launch_activation_ranges(const std::vector<BnDesc>& layers, float n_sigma, int32_t bits,
-                             squant_act_range_t* d_ranges, BnDesc* d_table, hipStream_t st) {
-  for (size_t c0 = 0; c0 < layers.size(); c0 += kBnChunk) {
-    BnChunk chunk{};
-    const int cnt = (int)std::min<size_t>(kBnChunk, layers.size() - c0);
-    for (int i = 0; i < cnt; ++i) chunk.t[i] = layers[c0 + i];
-    hipLaunchKernelGGL(write_bn_table, dim3(1), dim3(kBnChunk), 0, st, chunk, cnt, d_table + c0);
+                             squant_act_range_t* d_ranges, hipStream_t st) {
+  for (size_t c0 = 0; c0 < layers.size(); c0 += kInlineBn) {
+    BnArgs a{};
+    const int cnt = (int)std::min<size_t>(kInlineBn, layers.size() - c0);
+    for (int i = 0; i < cnt; ++i) a.layer[i] = layers[c0 + i];
+    a.n_sigma = n_sigma;
+    a.levels_minus_1 = (int32_t)((1 << bits) - 1);
+    a.out = d_ranges;
+    hipLaunchKernelGGL(squant_activation_range_kernel, dim3((unsigned)cnt), dim3(256), 0, st, a);
     if (hipGetLastError() != hipSuccess) return SQUANT_ERR_DEVICE;
   }
-  hipLaunchKernelGGL(squant_activation_range_kernel, dim3((unsigned)layers.size()), dim3(256), 0, st,
-                     d_table, n_sigma, (int32_t)((1 << bits) - 1), d_ranges);
-  if (hipGetLastError() != hipSuccess) return SQUANT_ERR_DEVICE;
   return SQUANT_OK;
 }
 
@@ -433,8 +426,7 @@ int squant_activation_ranges(const squant_bn_t* h_layers, int32_t n_layers, floa
   if (!d_workspace || workspace_bytes < squant_activation_workspace_bytes(n_layers) ||
       (reinterpret_cast<uintptr_t>(d_workspace) & 15u) != 0)
     return SQUANT_ERR_WORKSPACE;
-  return launch_activation_ranges(layers, n_sigma, bits, d_ranges, static_cast<BnDesc*>(d_workspace),
-                                  (hipStream_t)stream);
+  return launch_activation_ranges(layers, n_sigma, bits, d_ranges, (hipStream_t)stream);
 }
 
 size_t squant_network_workspace_bytes(int32_t n_layers) {
@@ -469,9 +461,7 @@ int squant_quantize_network(const squant_layer_t* h_layers, int32_t n_layers, in
                                        stream))
     return rc;
   if (bns.empty()) return SQUANT_OK;
-  return launch_activation_ranges(bns, n_sigma, act_bits, d_ranges,
-                                  reinterpret_cast<BnDesc*>(static_cast<char*>(d_workspace) + w_bytes),
-                                  (hipStream_t)stream);
+  return launch_activation_ranges(bns, n_sigma, act_bits, d_ranges, (hipStream_t)stream);
 }
 
 int64_t squant_max_channel_elems(int32_t kh, int32_t kw) {
@@ -538,6 +528,6 @@ const char* squant_status_string(int status) {
   }
 }
 
-int squant_version(void) { return 123; }
+int squant_version(void) { return 124; }
 
 }  // extern "C"
