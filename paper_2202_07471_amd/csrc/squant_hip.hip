@@ -122,7 +122,8 @@ Plan plan_tensor(const void* w, const void* out, int64_t N, int64_t K, int lds_l
       const int nv = variant == kK1x1 ? 1 : variant == kK1x2 ? 2 : variant == kK1x4 ? 4 : 8;
       return Plan{variant, (int)round_up64((N / 4 + nv - 1) / nv), round_up((size_t)N, 16)};
     }
-    case kDw9: return Plan{kDw9, kWave, 16};  // no LDS; 16 stands for "fits"
+    case kDw9: return Plan{kDw9, kWave, 16};     // no LDS; 16 stands for "fits"
+    case kK1Team: return Plan{kK1Team, kWave, 16};
     case kK1Stream: {
       const size_t lds = round_up((size_t)N, 16);  // the channel's int8 codes
       if (lds + sizeof(K9Shared) + 64 > (size_t)lds_limit) return Plan{kK1Stream, 0, 0};
@@ -148,10 +149,13 @@ int launch_part(const Group& g, size_t begin, size_t end, int qmax, int mode, in
   LaunchArgs a{};
   int64_t total = 0;
   bool uniform = true;
-  const int64_t items0 = work_items(g.t[begin].M, g.t[begin].N, g.t[begin].K, g.threads);
+  auto items_of = [&](const TensorDesc& t) {
+    return work_items(t.M, t.N, t.K, g.threads, choose_family(t.N, t.K, pointers_aligned(t.w, t.out)));
+  };
+  const int64_t items0 = items_of(g.t[begin]);
   for (size_t i = begin; i < end; ++i) {
     const TensorDesc& t = g.t[i];
-    const int64_t items = work_items(t.M, t.N, t.K, g.threads);
+    const int64_t items = items_of(t);
     a.table[i - begin] = t;
     a.table[i - begin].first = (int32_t)total;  // first workgroup within this launch
     total += items;
@@ -187,6 +191,8 @@ int launch_part(const Group& g, size_t begin, size_t end, int qmax, int mode, in
 #undef SQ_K1_ROW
   static const kernel_t k1s[4] = {squant_channel_k1_stream<SQUANT_MODE_E>, squant_channel_k1_stream<SQUANT_MODE_E>,
                                   squant_channel_k1_stream<SQUANT_MODE_EKC>, squant_channel_k1_stream<SQUANT_MODE_EKC>};
+  static const kernel_t k1team[4] = {squant_channel_k1_team<SQUANT_MODE_E>, squant_channel_k1_team<SQUANT_MODE_E>,
+                                     squant_channel_k1_team<SQUANT_MODE_EKC>, squant_channel_k1_team<SQUANT_MODE_EKC>};
   static const kernel_t dw9[4] = {squant_channel_dw9<SQUANT_MODE_E>, squant_channel_dw9<SQUANT_MODE_EK>,
                                   squant_channel_dw9<SQUANT_MODE_EKC>, squant_channel_dw9<SQUANT_MODE_EC>};
   static const kernel_t mixed[4] = {squant_channel_mixed<SQUANT_MODE_E>, squant_channel_mixed<SQUANT_MODE_EK>,
@@ -198,6 +204,7 @@ int launch_part(const Group& g, size_t begin, size_t end, int qmax, int mode, in
                           : g.variant == kK1x8 ? (g.threads <= 256 ? k1x8_small[mode] : k1x8[mode])
                           : g.variant == kK1Stream ? k1s[mode]
                           : g.variant == kDw9 ? dw9[mode]
+                          : g.variant == kK1Team ? k1team[mode]
                           : g.variant == kK9x1 ? k9x1[mode]
                           : g.variant == kK9x2 ? k9x2[mode]
                           : g.variant == kK9x4 ? (g.threads <= 256 ? k9x4[mode] : k9x4_large[mode])
@@ -528,6 +535,6 @@ const char* squant_status_string(int status) {
   }
 }
 
-int squant_version(void) { return 124; }
+int squant_version(void) { return 125; }
 
 }  // extern "C"

@@ -7,6 +7,7 @@
 
 #include "squant_generic.h"
 #include "squant_k1.h"
+#include "squant_k1_team.h"
 #include "squant_k9.h"
 #include "squant_plan.h"
 
@@ -40,6 +41,8 @@ __global__ void __launch_bounds__(kMixedMaxThreads) squant_channel_mixed(LaunchA
     else k1_channel<M1, 4>(a, d, m, smem, sh);
   } else if (family == 3) {
     dw9_channels<MODE>(a, d, m);
+  } else if (family == 4) {
+    k1_team_dispatch<M1>(a, d, m);
   } else {
     generic_channel(a, d, m, smem, gs);
   }

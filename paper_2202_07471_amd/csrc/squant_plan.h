@@ -14,20 +14,23 @@ enum Variant {
   kK9x1 = 1, kK9x2 = 2, kK9x4 = 3,             // 3x3 kernels per thread: 1, 2, 4
   kK1x1 = 4, kK1x2 = 5, kK1x4 = 6, kK1x8 = 7,  // 1x1 / FC: 16-byte vectors per thread: 1, 2, 4, 8
   kK1Stream = 8,                               // 1x1 / FC beyond kMaxK1Cin: weights walked repeatedly
-  kDw9 = 9                                     // depthwise 3x3 (cin per group = 1): one thread per channel
+  kDw9 = 9,                                    // depthwise 3x3 (cin per group = 1): one thread per channel
+  kK1Team = 10                                 // 1x1 / FC up to kMaxTeamCin: 4 to 16 channels per wave
 };
 
 constexpr int kMaxK9Cin = 4096;   // 3x3 variant: cin % 4 == 0 up to here
 constexpr int kMaxK1Cin = 32768;  // 1x1 variant: cin % 4 == 0 up to here
+constexpr int kMaxTeamCin = 256;  // 1x1 channels this short share a wave
 
 SQ_HD int64_t round_up64(int64_t v) { return (v + 63) / 64 * 64; }
 
 // Kernel family of a tensor: 9 = the 3x3 kernel, 1 = the 1x1 / FC kernel, 2 = the streaming
-// 1x1 / FC kernel, 3 = depthwise 3x3, 0 = generic.
+// 1x1 / FC kernel, 3 = depthwise 3x3, 4 = short 1x1 / FC channels (several per wave), 0 = generic.
 // aligned: weights on 16 bytes and output on 4 (what the vector loads / stores need)
 SQ_HD int choose_family(int64_t N, int64_t K, bool aligned) {
   if (K == 9 && N == 1) return 3;  // any alignment: element-wise loads and stores
   if (K == 9 && (N & 3) == 0 && N <= kMaxK9Cin && aligned) return 9;
+  if (K == 1 && (N & 3) == 0 && N <= kMaxTeamCin && aligned) return 4;
   if (K == 1 && (N & 3) == 0 && N <= kMaxK1Cin && aligned) return 1;
   if (K == 1 && (N & 3) == 0 && aligned) return 2;
   return 0;
@@ -59,13 +62,21 @@ SQ_HD int choose_variant(int64_t N, int64_t K, bool aligned) {
   }
   if (family == 2) return kK1Stream;
   if (family == 3) return kDw9;
+  if (family == 4) return kK1Team;
   return kGeneric;
 }
 
+// Lanes that share a short 1x1 channel (see squant_k1_team.h).
+SQ_HD int team_lanes(int64_t N) { return N <= 16 ? 4 : N <= 32 ? 8 : 16; }
+
 // Workgroups a tensor of M output channels takes in a launch of T threads per workgroup:
-// one per channel, except depthwise 3x3 where every thread has a channel of its own.
-SQ_HD int64_t work_items(int64_t M, int64_t N, int64_t K, int64_t T) {
-  return (K == 9 && N == 1) ? (M + T - 1) / T : M;
+// one per channel, except depthwise 3x3 (every thread has a channel of its own) and short
+// 1x1 channels (one per team of lanes).  `family` as from choose_family.
+SQ_HD int64_t work_items(int64_t M, int64_t N, int64_t K, int64_t T, int family) {
+  if (family == 3) return (M + T - 1) / T;
+  if (family == 4) { const int64_t per = T / team_lanes(N); return (M + per - 1) / per; }
+  (void)K;
+  return M;
 }
 
 SQ_HD bool pointers_aligned(const void* w, const void* out) {
