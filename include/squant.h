@@ -32,6 +32,8 @@
  *     no state between calls (the opt-in kernel timer below excepted);
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream); calls
  *     enqueue work and return; outputs are valid once the stream has been synchronised;
+ *     the calls only launch kernels (no allocation, no memset, no host synchronisation),
+ *     so they may be captured into a HIP graph (with the kernel timer off);
  *   - codes must not alias the weights; inputs must be finite (NaN/Inf: memory
  *     safe, result unspecified);
  *   - arguments are checked on the host before anything is launched and an

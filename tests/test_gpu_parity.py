@@ -220,6 +220,32 @@ def test_caller_stream_is_honoured(sq):
     assert_same(c2, sc2, w2, 8, 2, what="stream 2")
 
 
+def test_batched_call_in_a_hip_graph(sq):
+    """The calls only enqueue kernels (no allocation, no host synchronisation, no memset), so a
+    caller can capture them into a graph.  Replays with new weights in the same buffers, with
+    eager work and synchronisations in between, must each match the reference."""
+    shapes = [(32, 64, 3, 3), (16, 256, 1, 1), (8, 1, 3, 3), (4, 3, 7, 7), (24, 512, 3, 3), (6, 1028, 1, 1)]
+    dws = [torch.zeros(sh, device="cuda") for sh in shapes]
+    plan = sq.BatchPlan(dws)
+    plan.run(4, 2)                                   # warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        plan.run(4, 2)
+    for rep in range(4):
+        ws = [rand_weights(sh, 1000 + 10 * rep + i, "heavy" if (rep + i) % 2 else "normal")
+              for i, sh in enumerate(shapes)]
+        for d, w in zip(dws, ws):
+            d.copy_(torch.from_numpy(w))
+        eager = sq.squant_quantize(dws[0], 4, 2)     # the program's own eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for w, c, sc in zip(ws, plan.codes, plan.scales):
+            assert_same(c, sc, w, 4, 2, what=f"graph replay {rep} {w.shape}")
+        assert torch.equal(eager[0], plan.codes[0])
+
+
 def test_config5_slice_batched(sq):
     specs = synth.config_specs(5, n_tensors=6)
     ws = [synth.generate(s) for s in specs]
