@@ -290,6 +290,18 @@ def test_config5_full_size_sampled(sq):
     for t in (7, 100, 200):
         assert int(codes[t].abs().max()) <= 7
         assert bool((scales[t] > 0).all())
+    # Eq. 6-8 recomputed in float64 from (weights, GPU codes, GPU scales) on whole tensors: every
+    # channel's perturbation sum within 0.5, every kernel's within 1.0, every element within one
+    # step of its quotient (the slack covers the binary32 division and the Q23 grid)
+    for t in sorted(sample_tensors):
+        w = host_keep[t].astype(np.float64)
+        c = codes[t].cpu().numpy().astype(np.float64)
+        s = scales[t].cpu().numpy().astype(np.float64)[:, None, None, None]
+        p = (c - w / s).reshape(shape[0], shape[1], -1)
+        eps = 2.0 ** -17
+        assert np.abs(p.sum((-1, -2))).max() <= 0.5 + shape[1] * 9 * eps
+        assert np.abs(p.sum(-1)).max() <= 1.0 + 9 * eps
+        assert np.abs(p).max() < 1.0 + eps
 
 
 @pytest.mark.parametrize("kind", ["normal", "heavy", "grid"])

@@ -37,3 +37,16 @@ def test_variant_choice_covers_every_shape(tmp_path):
     out = subprocess.run([exe], capture_output=True, text=True)
     assert out.returncode == 0, out.stdout + out.stderr
     assert "plan_mismatches=0" in out.stdout
+
+
+def test_reference_solver_under_sanitizers(tmp_path):
+    """The CPU reference, compiled with the address and undefined-behaviour sanitizers, over
+    assorted shapes, value patterns, modes and bit widths: nothing out of bounds, no overflow."""
+    exe = str(tmp_path / "oracle_sanitize")
+    subprocess.check_call(["g++", "-std=c++17", "-O1", "-g", "-fno-omit-frame-pointer",
+                           "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                           "-static-libasan", "-pthread",
+                           os.path.join(ROOT, "tests", "host_oracle_sanitize.cpp"), "-o", exe])
+    out = subprocess.run([exe], capture_output=True, text=True)
+    assert out.returncode == 0, out.stdout + out.stderr
+    assert "sanitized_runs=1008" in out.stdout
