@@ -188,6 +188,7 @@ int launch_part(const Group& g, size_t begin, size_t end, int qmax, int mode, in
   static const kernel_t k1x4[4] = SQ_K1_ROW(256, 4);
   static const kernel_t k1x8[4] = SQ_K1_ROW(1024, 8);
   static const kernel_t k1x8_small[4] = SQ_K1_ROW(256, 8);
+  static const kernel_t k1x8_mid[4] = SQ_K1_ROW(768, 8);
 #undef SQ_K1_ROW
   static const kernel_t k1s[4] = {squant_channel_k1_stream<SQUANT_MODE_E>, squant_channel_k1_stream<SQUANT_MODE_E>,
                                   squant_channel_k1_stream<SQUANT_MODE_EKC>, squant_channel_k1_stream<SQUANT_MODE_EKC>};
@@ -201,7 +202,7 @@ int launch_part(const Group& g, size_t begin, size_t end, int qmax, int mode, in
                           : g.variant == kK1x1 ? k1x1[mode]
                           : g.variant == kK1x2 ? k1x2[mode]
                           : g.variant == kK1x4 ? k1x4[mode]
-                          : g.variant == kK1x8 ? (g.threads <= 256 ? k1x8_small[mode] : k1x8[mode])
+                          : g.variant == kK1x8 ? (g.threads <= 256 ? k1x8_small[mode] : g.threads <= 768 ? k1x8_mid[mode] : k1x8[mode])
                           : g.variant == kK1Stream ? k1s[mode]
                           : g.variant == kDw9 ? dw9[mode]
                           : g.variant == kK1Team ? k1team[mode]
@@ -543,6 +544,6 @@ const char* squant_status_string(int status) {
   }
 }
 
-int squant_version(void) { return 125; }
+int squant_version(void) { return 126; }
 
 }  // extern "C"

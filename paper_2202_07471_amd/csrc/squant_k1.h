@@ -245,6 +245,33 @@ __device__ __forceinline__ void k1_channel_stage(const int32_t (&P)[NE], int sgn
   }
 }
 
+// SQuant-E for the NV vectors of a thread: straight-line code per division method (FAST: the
+// quotients through the reciprocal rs = 1/s), chosen once per workgroup by the caller.
+template <int NV, bool FAST, bool WITH_P>
+__device__ __forceinline__ void k1_round_all(const float (&w)[4 * NV], float s, float rs, float qmaxf,
+                                             uint32_t* code32, int tid, int T, int nvec,
+                                             int32_t (&P)[4 * NV], int32_t& esum) {
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    uint32_t packed = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float wv = w[4 * j + e];
+      const float x = FAST ? div_by_reciprocal(wv, s, rs) : wv / s;  // the IEEE quotient either way
+      const float xc = __builtin_amdgcn_fmed3f(x, -qmaxf, qmaxf);
+      const float c = rintf(xc);
+      packed = __builtin_amdgcn_cvt_pk_u8_f32(c + 128.0f, e, packed);
+      if (WITH_P) {
+        const float p = c - xc;  // exact
+        P[4 * j + e] = __float_as_int(__builtin_fmaf(p, 8388608.0f, 12582912.0f)) - 0x4B400000;
+        esum += P[4 * j + e];
+      }
+    }
+    const int idx = tid + j * T;
+    if (idx < nvec) code32[idx] = packed;
+  }
+}
+
 template <int MODE, int NV>
 __device__ __forceinline__ void k1_channel(const LaunchArgs& a, const TensorDesc& d, int m,
                                            unsigned char* smem, K9Shared& sh) {
@@ -288,28 +315,11 @@ __device__ __forceinline__ void k1_channel(const LaunchArgs& a, const TensorDesc
   const bool fast = amax >= 0x1p-60f && amax <= 0x1p60f;  // uniform over the workgroup
   const float rs = 1.0f / s;
 
-  // ---- SQuant-E (Algorithm 1): code, and the element's perturbation as candidate word ----
+  // ---- SQuant-E (Algorithm 1): codes to LDS, perturbations kept in registers ----
   int32_t esum = 0;
   int32_t P[NE];
-#pragma unroll
-  for (int j = 0; j < NV; ++j) {
-    uint32_t packed = 0;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const float wv = w[4 * j + e];
-      const float x = fast ? div_by_reciprocal(wv, s, rs) : wv / s;  // the IEEE quotient either way
-      const float xc = __builtin_amdgcn_fmed3f(x, -qmaxf, qmaxf);
-      const float c = rintf(xc);
-      packed = __builtin_amdgcn_cvt_pk_u8_f32(c + 128.0f, e, packed);
-      if (kChannelStage) {
-        const float p = c - xc;  // exact
-        P[4 * j + e] = __float_as_int(__builtin_fmaf(p, 8388608.0f, 12582912.0f)) - 0x4B400000;
-        esum += P[4 * j + e];
-      }
-    }
-    const int idx = tid + j * T;
-    if (idx < nvec) code32[idx] = packed;
-  }
+  if (fast) k1_round_all<NV, true, kChannelStage>(w, s, rs, qmaxf, code32, tid, T, nvec, P, esum);
+  else k1_round_all<NV, false, kChannelStage>(w, s, rs, qmaxf, code32, tid, T, nvec, P, esum);
 
   if (kChannelStage) {
     // elements past the channel's end were loaded as 0, so their P is 0: no candidate
@@ -329,10 +339,14 @@ __device__ __forceinline__ void k1_channel(const LaunchArgs& a, const TensorDesc
 // unrolled per-element code otherwise spreads over ~95): measured 8-17 % faster from
 // cin = 1024 up, the extra waves hide the load latency.  The eight-vector variant is compiled
 // for five waves per SIMD in its 256-thread form (cin up to 8192; 4 and 6 were measured
-// slower) and keeps the 128 VGPRs that 16 waves per workgroup allow in its 1024-thread form.
+// slower), for six in its 768-thread form and keeps the 128 VGPRs that 16 waves per workgroup
+// allow in its 1024-thread form.  The steps matter because whole workgroups must fit: at
+// 128 VGPRs a compute unit has 16 wave slots, so workgroups of 5 to 8 waves came two at a
+// time and those of 9 or more one at a time (a 2.8x cliff just above cin = 8192); at 80 VGPRs
+// there are 24 slots.
 template <int MAX_THREADS, int MODE, int NV>
 __global__ void __launch_bounds__(MAX_THREADS)
-    __attribute__((amdgpu_waves_per_eu(MAX_THREADS > 256 ? 4 : NV <= 4 ? 8 : 5))) squant_channel_k1(LaunchArgs a) {
+    __attribute__((amdgpu_waves_per_eu(MAX_THREADS > 768 ? 4 : MAX_THREADS > 256 ? 6 : NV <= 4 ? 8 : 5))) squant_channel_k1(LaunchArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];  // N bytes of biased codes
   __shared__ K9Shared sh;
   int m;
