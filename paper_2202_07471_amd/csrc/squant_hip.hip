@@ -23,6 +23,7 @@
 #include "squant_common.h"
 #include "squant_generic.h"
 #include "squant_k9.h"
+#include "squant_ks.h"
 #include "squant_k1.h"
 #include "squant_mixed.h"
 #include "squant_act.h"
@@ -131,6 +132,8 @@ Plan plan_tensor(const void* w, const void* out, int64_t N, int64_t K, int lds_l
     }
     default: break;
   }
+  if (is_ks(variant))  // LDS: the channel's int8 codes
+    return Plan{variant, (int)round_up64(N / ks_variant_kpt(variant)), round_up((size_t)K * N, 16)};
   const size_t lds = generic_lds_bytes(N, K);
   if (lds + kStaticLds > (size_t)lds_limit) return Plan{kGeneric, 0, 0};
   return Plan{kGeneric, generic_threads(N, K), lds};
@@ -139,8 +142,50 @@ Plan plan_tensor(const void* w, const void* out, int64_t N, int64_t K, int lds_l
 // Whether a tensor may join a launch of the mixed kernel: its variant is one the mixed kernel
 // carries (all but the eight-vector 1x1 variant) and fits its workgroup size and LDS.
 bool mixable(const Plan& p, size_t lds_cap) {
-  return p.variant != kK1x8 && p.variant != kK1Stream && p.threads <= kMixedMaxThreads &&
+  return p.variant != kK1x8 && p.variant != kK1Stream && !is_ks(p.variant) &&
+         p.threads <= kMixedMaxThreads &&
          p.lds <= lds_cap;
+}
+
+typedef void (*kernel_t)(LaunchArgs);
+
+// The small-kernel variant's instantiation for (K, kernels per thread), workgroup size and mode.
+template <int K, int KPT>
+kernel_t ks_kernel_of(int threads, int mode, bool largest) {
+#define SQ_KS_ROW(T)                                                                          \
+  {squant_channel_ks<T, SQUANT_MODE_E, K, KPT>, squant_channel_ks<T, SQUANT_MODE_EK, K, KPT>, \
+   squant_channel_ks<T, SQUANT_MODE_EKC, K, KPT>, squant_channel_ks<T, SQUANT_MODE_EC, K, KPT>}
+  static const kernel_t small[4] = SQ_KS_ROW(256);
+  if (threads <= 256 || !largest) return small[mode];
+  if constexpr (KPT == (K <= 4 ? 8 : 4)) {
+    static const kernel_t large[4] = SQ_KS_ROW(1024);
+    return large[mode];
+  }
+#undef SQ_KS_ROW
+  return small[mode];
+}
+template <int K>
+kernel_t ks_kernel_k(int kpt, int threads, int mode) {
+  const bool largest = kpt == (1 << ks_max_kpt_log2(K));
+  switch (kpt) {
+    case 1: return ks_kernel_of<K, 1>(threads, mode, largest);
+    case 2: return ks_kernel_of<K, 2>(threads, mode, largest);
+    case 4: return ks_kernel_of<K, 4>(threads, mode, largest);
+    default:
+      if constexpr (K <= 4) return ks_kernel_of<K, 8>(threads, mode, largest);
+      return nullptr;
+  }
+}
+kernel_t ks_kernel(int variant, int threads, int mode) {
+  const int kpt = ks_variant_kpt(variant);
+  switch (ks_variant_k(variant)) {
+    case 2: return ks_kernel_k<2>(kpt, threads, mode);
+    case 3: return ks_kernel_k<3>(kpt, threads, mode);
+    case 4: return ks_kernel_k<4>(kpt, threads, mode);
+    case 5: return ks_kernel_k<5>(kpt, threads, mode);
+    case 7: return ks_kernel_k<7>(kpt, threads, mode);
+    default: return nullptr;
+  }
 }
 
 // Launches tensors [begin, end) of a group (at most kInlineDescs of them) as one kernel.
@@ -170,7 +215,6 @@ int launch_part(const Group& g, size_t begin, size_t end, int qmax, int mode, in
   a.mode = mode;
   a.out_format = output;
   a.wtype = wtype;
-  typedef void (*kernel_t)(LaunchArgs);
 #define SQ_K9_ROW(T, KPT)                                                                     \
   {squant_channel_k9<T, SQUANT_MODE_E, KPT>, squant_channel_k9<T, SQUANT_MODE_EK, KPT>,       \
    squant_channel_k9<T, SQUANT_MODE_EKC, KPT>, squant_channel_k9<T, SQUANT_MODE_EC, KPT>}
@@ -198,7 +242,8 @@ int launch_part(const Group& g, size_t begin, size_t end, int qmax, int mode, in
                                   squant_channel_dw9<SQUANT_MODE_EKC>, squant_channel_dw9<SQUANT_MODE_EC>};
   static const kernel_t mixed[4] = {squant_channel_mixed<SQUANT_MODE_E>, squant_channel_mixed<SQUANT_MODE_EK>,
                                     squant_channel_mixed<SQUANT_MODE_EKC>, squant_channel_mixed<SQUANT_MODE_EC>};
-  const kernel_t kernel = (g.variant == kMixed || g.variant == kMixedWave) ? mixed[mode]
+  const kernel_t kernel = is_ks(g.variant) ? ks_kernel(g.variant, g.threads, mode)
+                          : (g.variant == kMixed || g.variant == kMixedWave) ? mixed[mode]
                           : g.variant == kK1x1 ? k1x1[mode]
                           : g.variant == kK1x2 ? k1x2[mode]
                           : g.variant == kK1x4 ? k1x4[mode]
@@ -210,6 +255,7 @@ int launch_part(const Group& g, size_t begin, size_t end, int qmax, int mode, in
                           : g.variant == kK9x2 ? k9x2[mode]
                           : g.variant == kK9x4 ? (g.threads <= 256 ? k9x4[mode] : k9x4_large[mode])
                                                : squant_channel_generic;
+  if (!kernel) return SQUANT_ERR_UNSUPPORTED;
   if (g.lds > 48 * 1024) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds) != hipSuccess) {

@@ -15,7 +15,8 @@ enum Variant {
   kK1x1 = 4, kK1x2 = 5, kK1x4 = 6, kK1x8 = 7,  // 1x1 / FC: 16-byte vectors per thread: 1, 2, 4, 8
   kK1Stream = 8,                               // 1x1 / FC beyond kMaxK1Cin: weights walked repeatedly
   kDw9 = 9,                                    // depthwise 3x3 (cin per group = 1): one thread per channel
-  kK1Team = 10                                 // 1x1 / FC up to kMaxTeamCin: 4 to 16 channels per wave
+  kK1Team = 10,                                // 1x1 / FC up to kMaxTeamCin: 4 to 16 channels per wave
+  kKs = 64                                     // small kernels in registers: kKs + 4 * K + log2(kernels per thread)
 };
 
 constexpr int kMaxK9Cin = 4096;   // 3x3 variant: cin % 4 == 0 up to here
@@ -24,8 +25,40 @@ constexpr int kMaxTeamCin = 256;  // 1x1 channels this short share a wave
 
 SQ_HD int64_t round_up64(int64_t v) { return (v + 63) / 64 * 64; }
 
+// Small kernels held in registers (squant_ks.h): the kernel sizes it is built for, and the
+// largest power of two (as its logarithm) of kernels one thread holds.
+constexpr int kKsMaxK = 7;
+SQ_HD bool ks_has(int64_t K) { return K == 2 || K == 3 || K == 4 || K == 5 || K == 7; }
+SQ_HD int ks_max_kpt_log2(int64_t K) { return K <= 4 ? 3 : 2; }
+// log2 of the kernels per thread for a channel of N such kernels: the largest power of two that
+// divides N and leaves the waves at least 60 % full, else the one that keeps them fullest
+// (measured: fewer, longer threads win down to that fill: 1x7 with cin 192 and 1x3 with cin 384
+// 10 % faster at 75 % than at 100 %, 1x7 with cin 160 13 % faster at 62 % than at 83 %, cin 128
+// 50 % slower at 50 % than at 100 %); only the largest one is built for workgroups beyond
+// 256 threads.  -1: none fits (then the generic kernel takes the tensor).
+SQ_HD int ks_kpt_log2(int64_t N, int64_t K) {
+  if (!ks_has(K) || ((N * K) & 3) != 0) return -1;
+  const int top = ks_max_kpt_log2(K);
+  int best = -1;
+  int64_t best_num = 0, best_den = 1;
+  for (int lg = top; lg >= 0; --lg) {
+    const int64_t c = (int64_t)1 << lg;
+    if (N % c != 0) continue;
+    const int64_t th = round_up64(N / c);
+    if (th > 1024 || (th > 256 && lg != top)) continue;
+    if ((N / c) * 10 >= th * 6) return lg;
+    if ((N / c) * best_den > best_num * th) { best_num = N / c; best_den = th; best = lg; }
+  }
+  return best;
+}
+SQ_HD bool is_ks(int variant) { return variant >= kKs && variant < kKs + 4 * (kKsMaxK + 1); }
+SQ_HD int ks_variant(int64_t K, int kpt_log2) { return kKs + 4 * (int)K + kpt_log2; }
+SQ_HD int ks_variant_k(int variant) { return (variant - kKs) >> 2; }
+SQ_HD int ks_variant_kpt(int variant) { return 1 << ((variant - kKs) & 3); }
+
 // Kernel family of a tensor: 9 = the 3x3 kernel, 1 = the 1x1 / FC kernel, 2 = the streaming
-// 1x1 / FC kernel, 3 = depthwise 3x3, 4 = short 1x1 / FC channels (several per wave), 0 = generic.
+// 1x1 / FC kernel, 3 = depthwise 3x3, 4 = short 1x1 / FC channels (several per wave), 5 = other
+// small kernels in registers, 0 = generic.
 // aligned: weights on 16 bytes and output on 4 (what the vector loads / stores need)
 SQ_HD int choose_family(int64_t N, int64_t K, bool aligned) {
   if (K == 9 && N == 1) return 3;  // any alignment: element-wise loads and stores
@@ -33,6 +66,7 @@ SQ_HD int choose_family(int64_t N, int64_t K, bool aligned) {
   if (K == 1 && (N & 3) == 0 && N <= kMaxTeamCin && aligned) return 4;
   if (K == 1 && (N & 3) == 0 && N <= kMaxK1Cin && aligned) return 1;
   if (K == 1 && (N & 3) == 0 && aligned) return 2;
+  if (N > 1 && aligned && ks_kpt_log2(N, K) >= 0) return 5;
   return 0;
 }
 
@@ -63,6 +97,7 @@ SQ_HD int choose_variant(int64_t N, int64_t K, bool aligned) {
   if (family == 2) return kK1Stream;
   if (family == 3) return kDw9;
   if (family == 4) return kK1Team;
+  if (family == 5) return ks_variant(K, ks_kpt_log2(N, K));
   return kGeneric;
 }
 

@@ -10,9 +10,9 @@
 using namespace squant;
 
 int main() {
-  long bad = 0, k9 = 0, k1 = 0, stream = 0, team = 0, generic = 0;
+  long bad = 0, k9 = 0, k1 = 0, stream = 0, team = 0, small = 0, generic = 0;
   for (int aligned = 0; aligned < 2; ++aligned)
-    for (int64_t K : {1, 2, 4, 9, 25, 49})
+    for (int64_t K : {1, 2, 3, 4, 5, 6, 7, 8, 9, 25, 49})
       for (int64_t N = 1; N <= 40000; N += (N < 600 ? 1 : 61)) {
         const int family = choose_family(N, K, aligned != 0);
         const int v = choose_variant(N, K, aligned != 0);
@@ -51,13 +51,47 @@ int main() {
         } else if (family == 2) {
           ++stream;  // a 1x1 channel too long for the register-resident kernel
           bad += v != kK1Stream || K != 1 || !aligned || N % 4 || N <= kMaxK1Cin;
+        } else if (family == 5) {
+          ++small;  // other small kernels in registers
+          if (!is_ks(v) || !aligned || !ks_has(K) || (N * K) % 4 || N < 2 || K > kKsMaxK) { ++bad; continue; }
+          const int kpt = ks_variant_kpt(v), top = 1 << ks_max_kpt_log2(K);
+          bad += ks_variant_k(v) != K || v != ks_variant(K, ks_kpt_log2(N, K));
+          bad += kpt < 1 || kpt > top || (kpt & (kpt - 1)) != 0;
+          bad += N % kpt != 0;                 // every thread owns whole kernels
+          const int64_t threads = round_up64(N / kpt);
+          bad += threads * kpt < N || threads > 1024;
+          bad += kpt != top && threads > 256;  // only the largest is built for 1024 threads
+          bad += K * kpt > 32;                 // elements a thread holds in registers
+          bool roomy = false;                  // some admissible choice leaves the waves 60 % full
+          for (int c = 1; c <= top; c *= 2) {
+            if (N % c) continue;
+            const int64_t th = round_up64(N / c);
+            if (th > 1024 || (th > 256 && c != top)) continue;
+            const bool ok60 = (N / c) * 10 >= th * 6;
+            roomy |= ok60;
+            bad += ok60 && c > kpt;            // the largest such count is the one taken
+          }
+          if (roomy) {
+            bad += (N / kpt) * 10 < threads * 6;
+          } else {                             // else none keeps the waves fuller
+            for (int c = 1; c <= top; c *= 2) {
+              if (N % c) continue;
+              const int64_t th = round_up64(N / c);
+              if (th > 1024 || (th > 256 && c != top)) continue;
+              bad += (N / c) * threads > (N / kpt) * th;
+            }
+          }
+          bad += work_items(130, N, K, threads, family) != 130;
         } else {
           ++generic;
           bad += v != kGeneric || work_items(130, N, K, 64, family) != 130;
           bad += aligned && K == 9 && N % 4 == 0 && N <= kMaxK9Cin;
           bad += aligned && K == 1 && N % 4 == 0;
+          bad += aligned && ks_has(K) && N > 1 && (N * K) % 4 == 0 && N <= 256;  // one kernel per thread always fits
         }
       }
-  std::printf("plan_mismatches=%ld k9=%ld k1=%ld stream=%ld team=%ld generic=%ld\n", bad, k9, k1, stream, team, generic);
+  std::printf("plan_mismatches=%ld k9=%ld k1=%ld stream=%ld team=%ld small=%ld generic=%ld\n", bad, k9, k1, stream,
+              team, small, generic);
+  bad += small == 0;
   return bad != 0;
 }
