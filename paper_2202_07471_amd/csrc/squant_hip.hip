@@ -157,7 +157,7 @@ kernel_t ks_kernel_of(int threads, int mode, bool largest) {
    squant_channel_ks<T, SQUANT_MODE_EKC, K, KPT>, squant_channel_ks<T, SQUANT_MODE_EC, K, KPT>}
   static const kernel_t small[4] = SQ_KS_ROW(256);
   if (threads <= 256 || !largest) return small[mode];
-  if constexpr (KPT == (K <= 4 ? 8 : 4)) {
+  if constexpr (KPT == (1 << ks_max_kpt_log2(K))) {
     static const kernel_t large[4] = SQ_KS_ROW(1024);
     return large[mode];
   }
@@ -167,14 +167,12 @@ kernel_t ks_kernel_of(int threads, int mode, bool largest) {
 template <int K>
 kernel_t ks_kernel_k(int kpt, int threads, int mode) {
   const bool largest = kpt == (1 << ks_max_kpt_log2(K));
-  switch (kpt) {
-    case 1: return ks_kernel_of<K, 1>(threads, mode, largest);
-    case 2: return ks_kernel_of<K, 2>(threads, mode, largest);
-    case 4: return ks_kernel_of<K, 4>(threads, mode, largest);
-    default:
-      if constexpr (K <= 4) return ks_kernel_of<K, 8>(threads, mode, largest);
-      return nullptr;
-  }
+  constexpr int top = 1 << ks_max_kpt_log2(K);
+  if (kpt == 1) return ks_kernel_of<K, 1>(threads, mode, largest);
+  if constexpr (top >= 2) if (kpt == 2) return ks_kernel_of<K, 2>(threads, mode, largest);
+  if constexpr (top >= 4) if (kpt == 4) return ks_kernel_of<K, 4>(threads, mode, largest);
+  if constexpr (top >= 8) if (kpt == 8) return ks_kernel_of<K, 8>(threads, mode, largest);
+  return nullptr;
 }
 kernel_t ks_kernel(int variant, int threads, int mode) {
   const int kpt = ks_variant_kpt(variant);
@@ -184,6 +182,7 @@ kernel_t ks_kernel(int variant, int threads, int mode) {
     case 4: return ks_kernel_k<4>(kpt, threads, mode);
     case 5: return ks_kernel_k<5>(kpt, threads, mode);
     case 7: return ks_kernel_k<7>(kpt, threads, mode);
+    case 25: return ks_kernel_k<25>(kpt, threads, mode);
     default: return nullptr;
   }
 }

@@ -16,7 +16,7 @@ enum Variant {
   kK1Stream = 8,                               // 1x1 / FC beyond kMaxK1Cin: weights walked repeatedly
   kDw9 = 9,                                    // depthwise 3x3 (cin per group = 1): one thread per channel
   kK1Team = 10,                                // 1x1 / FC up to kMaxTeamCin: 4 to 16 channels per wave
-  kKs = 64                                     // small kernels in registers: kKs + 4 * K + log2(kernels per thread)
+  kKs = 1024                                   // small kernels in registers: kKs + 4 * K + log2(kernels per thread)
 };
 
 constexpr int kMaxK9Cin = 4096;   // 3x3 variant: cin % 4 == 0 up to here
@@ -27,9 +27,9 @@ SQ_HD int64_t round_up64(int64_t v) { return (v + 63) / 64 * 64; }
 
 // Small kernels held in registers (squant_ks.h): the kernel sizes it is built for, and the
 // largest power of two (as its logarithm) of kernels one thread holds.
-constexpr int kKsMaxK = 7;
-SQ_HD bool ks_has(int64_t K) { return K == 2 || K == 3 || K == 4 || K == 5 || K == 7; }
-SQ_HD int ks_max_kpt_log2(int64_t K) { return K <= 4 ? 3 : 2; }
+constexpr int kKsMaxK = 25;
+SQ_HD bool ks_has(int64_t K) { return K == 2 || K == 3 || K == 4 || K == 5 || K == 7 || K == 25; }
+SQ_HD constexpr int ks_max_kpt_log2(int64_t K) { return K <= 4 ? 3 : K <= 7 ? 2 : 0; }
 // log2 of the kernels per thread for a channel of N such kernels: the largest power of two that
 // divides N and leaves the waves at least 60 % full, else the one that keeps them fullest
 // (measured: fewer, longer threads win down to that fill: 1x7 with cin 192 and 1x3 with cin 384

@@ -61,7 +61,7 @@ int main() {
           const int64_t threads = round_up64(N / kpt);
           bad += threads * kpt < N || threads > 1024;
           bad += kpt != top && threads > 256;  // only the largest is built for 1024 threads
-          bad += K * kpt > 32;                 // elements a thread holds in registers
+          bad += K * kpt > 32 && kpt > 1;      // elements a thread holds in registers
           bool roomy = false;                  // some admissible choice leaves the waves 60 % full
           for (int c = 1; c <= top; c *= 2) {
             if (N % c) continue;

@@ -57,9 +57,9 @@ def check(got, got_s, want, want_s, what):
                              f"gpu={got[tuple(bad[0])]} ref={want[tuple(bad[0])]}")
 
 
-# (kh, kw) with kh*kw in {2, 3, 4, 5, 7}; cin chosen to reach 1, 2, 4 and 8 kernels per thread,
+# (kh, kw) with kh*kw in {2, 3, 4, 5, 7, 25}; cin chosen to reach 1, 2, 4 and 8 kernels per thread,
 # partly filled waves, more than 256 threads (the 1024-thread instantiation) and its maximum
-KERNELS = [(1, 2), (1, 3), (3, 1), (2, 2), (1, 5), (1, 7), (7, 1), (4, 1)]
+KERNELS = [(1, 2), (1, 3), (3, 1), (2, 2), (1, 5), (1, 7), (7, 1), (4, 1), (5, 5)]
 CINS = [4, 8, 20, 64, 96, 128, 192, 384, 448, 1024, 2056, 4096]
 
 
@@ -68,6 +68,8 @@ CINS = [4, 8, 20, 64, 96, 128, 192, 384, 448, 1024, 2056, 4096]
 def test_small_kernels_every_width(sq, khw, kind):
     kh, kw = khw
     for cin in CINS:
+        if kh * kw == 25 and cin > 1024:      # 5x5: one kernel per thread, so cin <= 1024; beyond it the
+            cin = 1028 if cin == 2056 else 48  # generic kernel (1028 fits its LDS), and the common cin = 48
         cout = 5 if cin < 1024 else 3
         shape = (cout, cin, kh, kw)
         w = weights(shape, 97 + cin + 10 * kh + kw, kind)
@@ -79,12 +81,13 @@ def test_small_kernels_every_width(sq, khw, kind):
             check(got, got_s, want, want_s, f"{shape} {kind} bits={bits} mode={mode}")
 
 
-@pytest.mark.parametrize("khw", [(1, 3), (1, 7), (2, 2), (1, 5), (1, 2)])
+@pytest.mark.parametrize("khw", [(1, 3), (1, 7), (2, 2), (1, 5), (1, 2), (5, 5)])
 def test_small_kernels_largest_channels(sq, khw):
     kh, kw = khw
     K = kh * kw
-    cin = 1024 * (8 if K <= 4 else 4)           # the widest channel the variant takes
-    for c in (cin, cin - (8 if K <= 4 else 4), cin + 8):   # ... and its neighbours
+    top = 8 if K <= 4 else 4 if K <= 7 else 1   # most kernels one thread holds
+    cin = 1024 * top                            # the widest channel the variant takes
+    for c in (cin, cin - max(4, top), cin + 8):   # ... and its neighbours
         shape = (2, c, kh, kw)
         w = weights(shape, 5 + c + K, "normal")
         if c > cin and c * K > sq.squant_max_channel_elems(kh, kw):
@@ -112,7 +115,7 @@ def test_neighbouring_shapes_use_the_generic_kernel(sq, shape):
 
 @pytest.mark.parametrize("output", ["int4", "f32", "bf16"])
 @pytest.mark.parametrize("shape", [(5, 192, 1, 7), (5, 384, 3, 1), (4, 48, 1, 5), (6, 8, 2, 2), (3, 2052, 1, 3),
-                                   (5, 12, 1, 3), (4, 22, 1, 2)])
+                                   (5, 12, 1, 3), (4, 22, 1, 2), (5, 48, 5, 5)])
 def test_small_kernels_other_outputs(sq, shape, output):
     out = {"int4": sq.OUT_INT4, "f32": sq.OUT_F32, "bf16": sq.OUT_BF16}[output]
     for kind in ("normal", "grid"):
@@ -128,7 +131,7 @@ def test_small_kernels_other_outputs(sq, shape, output):
 
 @pytest.mark.parametrize("wtype", ["f16", "bf16"])
 @pytest.mark.parametrize("shape", [(5, 192, 1, 7), (5, 384, 3, 1), (4, 48, 1, 5), (6, 8, 2, 2), (3, 2052, 1, 3),
-                                   (4, 22, 1, 2)])
+                                   (4, 22, 1, 2), (5, 48, 5, 5)])
 def test_small_kernels_sixteen_bit_weights(sq, shape, wtype):
     for kind in ("normal", "grid"):
         t16 = torch.from_numpy(weights(shape, 53 + sum(shape), kind)).to(
@@ -143,7 +146,7 @@ def test_small_kernels_sixteen_bit_weights(sq, shape, wtype):
 
 def test_small_kernels_degenerate_channels(sq):
     # all-zero tensor, one non-zero weight, equal weights (every perturbation ties), exact halves
-    for kh, kw, cin in ((1, 3, 64), (1, 7, 32), (2, 2, 16), (1, 5, 12), (1, 2, 256)):
+    for kh, kw, cin in ((1, 3, 64), (1, 7, 32), (2, 2, 16), (1, 5, 12), (1, 2, 256), (5, 5, 8)):
         shape = (6, cin, kh, kw)
         w = np.zeros(shape, np.float32)
         w[1, 3, 0, 0] = -2.5
