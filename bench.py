@@ -26,6 +26,7 @@ WORKLOADS = {
     "c3": (3, "ResNet-50-shaped layer set (54 tensors), He-normal + 1% Laplace outliers"),
     "c4": (4, "MobileNetV2-shaped layer set (53 tensors), He-normal"),
     "c5": (5, "256 x [512,512,3,3] fp32, N(0,s) / Student-t(3) per tensor, one batched call"),
+    "c6": (6, "InceptionV3-style layer set (95 tensors: 1x7, 7x1, 1x3, 3x1, 5x5, 3x3, 1x1), He-normal"),
 }
 
 

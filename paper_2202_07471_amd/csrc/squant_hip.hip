@@ -97,6 +97,8 @@ void timer_mark(bool start, hipStream_t st);
 
 constexpr int kMixed = 100;      // Group::variant of a launch of squant_channel_mixed
 constexpr int kMixedWave = 101;  // the same for the tensors whose channels take one wave each
+constexpr int kKsMixed = 102;    // Group::variant of a launch of squant_channel_ks_mixed
+constexpr int kKsMixedMaxThreads = 128;
 
 struct Group {
   int variant;
@@ -241,7 +243,10 @@ int launch_part(const Group& g, size_t begin, size_t end, int qmax, int mode, in
                                   squant_channel_dw9<SQUANT_MODE_EKC>, squant_channel_dw9<SQUANT_MODE_EC>};
   static const kernel_t mixed[4] = {squant_channel_mixed<SQUANT_MODE_E>, squant_channel_mixed<SQUANT_MODE_EK>,
                                     squant_channel_mixed<SQUANT_MODE_EKC>, squant_channel_mixed<SQUANT_MODE_EC>};
+  static const kernel_t ksmixed[4] = {squant_channel_ks_mixed<SQUANT_MODE_E>, squant_channel_ks_mixed<SQUANT_MODE_EK>,
+                                      squant_channel_ks_mixed<SQUANT_MODE_EKC>, squant_channel_ks_mixed<SQUANT_MODE_EC>};
   const kernel_t kernel = is_ks(g.variant) ? ks_kernel(g.variant, g.threads, mode)
+                          : g.variant == kKsMixed ? ksmixed[mode]
                           : (g.variant == kMixed || g.variant == kMixedWave) ? mixed[mode]
                           : g.variant == kK1x1 ? k1x1[mode]
                           : g.variant == kK1x2 ? k1x2[mode]
@@ -391,6 +396,17 @@ int squant_quantize_batched_ex(const squant_tensor_t* h_tensors, int32_t n_tenso
     }
   }
   const bool use_mixed = small_kinds > 1;
+  // Likewise the small-kernel tensors of up to kKsMixedMaxThreads threads per channel share one
+  // launch when they differ in kernel size, kernels per thread or launch shape.
+  int ks_kinds = 0;
+  Plan ks_first{};
+  for (int32_t i = 0; i < n_tensors; ++i) {
+    const Plan& p = plans[(size_t)i];
+    if (!is_ks(p.variant) || p.threads > kKsMixedMaxThreads) continue;
+    if (ks_kinds == 0) { ks_first = p; ks_kinds = 1; }
+    else if (p.variant != ks_first.variant || p.threads != ks_first.threads || p.lds != ks_first.lds) ks_kinds = 2;
+  }
+  const bool use_ks_mixed = ks_kinds > 1;
   // One mixed launch while its workgroups stay at 128 threads (measured: ResNet-18 set 27 %,
   // MobileNetV2 set 12 % faster than two launches, ResNet-50 set the same).  When a member
   // needs 256 threads, the channels that take one wave get a launch of one-wave workgroups of
@@ -405,8 +421,9 @@ int squant_quantize_batched_ex(const squant_tensor_t* h_tensors, int32_t n_tenso
   for (int32_t i = 0; i < n_tensors; ++i) {
     const squant_tensor_t& t = h_tensors[i];
     const Plan& p = plans[(size_t)i];
-    const bool in_mixed = use_mixed && mixable(p, lds_cap);
-    const int mixed_kind = (two_classes && p.threads <= kWave) ? kMixedWave : kMixed;
+    const bool in_ks_mixed = use_ks_mixed && is_ks(p.variant) && p.threads <= kKsMixedMaxThreads;
+    const bool in_mixed = in_ks_mixed || (use_mixed && mixable(p, lds_cap));
+    const int mixed_kind = in_ks_mixed ? kKsMixed : (two_classes && p.threads <= kWave) ? kMixedWave : kMixed;
     Group* g = nullptr;
     for (auto& c : groups) {
       if (in_mixed ? c.variant == mixed_kind
@@ -589,6 +606,6 @@ const char* squant_status_string(int status) {
   }
 }
 
-int squant_version(void) { return 126; }
+int squant_version(void) { return 127; }
 
 }  // extern "C"

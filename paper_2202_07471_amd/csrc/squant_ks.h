@@ -14,6 +14,7 @@
 #include "squant_common.h"
 #include "squant_io.h"
 #include "squant_k9.h"  // K9Shared
+#include "squant_plan.h"
 #include "squant_select.h"
 
 namespace squant {
@@ -238,6 +239,30 @@ __global__ void __launch_bounds__(MAX_THREADS) squant_channel_ks(LaunchArgs a) {
   int m;
   const TensorDesc d = locate(a, blockIdx.x, m);
   ks_channel<MODE, K, KPT>(a, d, m, smem, sh);
+}
+
+// One launch for tensors of different small-kernel shapes (the factorised 1x7 / 7x1 / 1x3 / 3x1
+// and 5x5 layers of a network): every workgroup looks up its tensor and takes the routine for
+// its kernel size and kernels per thread.  The workgroup may be larger than a member needs;
+// its extra threads idle.
+template <int MODE>
+__global__ void __launch_bounds__(256) squant_channel_ks_mixed(LaunchArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  __shared__ K9Shared sh;
+  int m;
+  const TensorDesc d = locate(a, blockIdx.x, m);
+  switch (4 * d.K + ks_kpt_log2(d.N, d.K)) {
+#define SQ_KS_CASE(K, LG) \
+    case 4 * K + LG: ks_channel<MODE, K, (1 << LG)>(a, d, m, smem, sh); break;
+    SQ_KS_CASE(2, 0) SQ_KS_CASE(2, 1) SQ_KS_CASE(2, 2) SQ_KS_CASE(2, 3)
+    SQ_KS_CASE(3, 0) SQ_KS_CASE(3, 1) SQ_KS_CASE(3, 2) SQ_KS_CASE(3, 3)
+    SQ_KS_CASE(4, 0) SQ_KS_CASE(4, 1) SQ_KS_CASE(4, 2) SQ_KS_CASE(4, 3)
+    SQ_KS_CASE(5, 0) SQ_KS_CASE(5, 1) SQ_KS_CASE(5, 2)
+    SQ_KS_CASE(7, 0) SQ_KS_CASE(7, 1) SQ_KS_CASE(7, 2)
+    SQ_KS_CASE(25, 0)
+#undef SQ_KS_CASE
+    default: break;  // the host puts no other tensor into this launch
+  }
 }
 
 }  // namespace squant

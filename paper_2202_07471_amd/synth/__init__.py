@@ -141,6 +141,27 @@ def mobilenetv2_shapes() -> List[Shape]:
     return s
 
 
+def inceptionv3_shapes() -> List[Shape]:
+    """Factorised-convolution network in the style of InceptionV3 (main branch, no auxiliary
+    head): 1x7 / 7x1, 1x3 / 3x1 and 5x5 kernels beside 3x3 and 1x1 ones."""
+    s: List[Shape] = [(32, 3, 3, 3), (32, 32, 3, 3), (64, 32, 3, 3), (80, 64, 1, 1), (192, 80, 3, 3)]
+    for cin, pool in ((192, 32), (256, 64), (288, 64)):                 # 35 x 35 blocks
+        s += [(64, cin, 1, 1), (48, cin, 1, 1), (64, 48, 5, 5), (64, cin, 1, 1), (96, 64, 3, 3),
+              (96, 96, 3, 3), (pool, cin, 1, 1)]
+    s += [(384, 288, 3, 3), (64, 288, 1, 1), (96, 64, 3, 3), (96, 96, 3, 3)]   # reduction to 17 x 17
+    for c7 in (128, 160, 160, 192):                                     # 17 x 17 blocks
+        s += [(192, 768, 1, 1), (c7, 768, 1, 1), (c7, c7, 1, 7), (192, c7, 7, 1),
+              (c7, 768, 1, 1), (c7, c7, 7, 1), (c7, c7, 1, 7), (c7, c7, 7, 1), (192, c7, 1, 7),
+              (192, 768, 1, 1)]
+    s += [(192, 768, 1, 1), (320, 192, 3, 3), (192, 768, 1, 1), (192, 192, 1, 7), (192, 192, 7, 1),
+          (192, 192, 3, 3)]                                             # reduction to 8 x 8
+    for cin in (1280, 2048):                                            # 8 x 8 blocks
+        s += [(320, cin, 1, 1), (384, cin, 1, 1), (384, 384, 1, 3), (384, 384, 3, 1),
+              (448, cin, 1, 1), (384, 448, 3, 3), (384, 384, 1, 3), (384, 384, 3, 1), (192, cin, 1, 1)]
+    s.append((1000, 2048, 1, 1))
+    return s
+
+
 @dataclass(frozen=True)
 class TensorSpec:
     config: int
@@ -156,13 +177,14 @@ class TensorSpec:
 
 def config_specs(config: int, seed: int = DEFAULT_SEED, n_tensors: int | None = None
                  ) -> List[TensorSpec]:
-    """Tensor list of workload `config` (1..5).
+    """Tensor list of workload `config` (1..6).
 
     1: one [64,64,3,3] He-normal tensor.            2: ResNet-18 layer set, He-normal.
     3: ResNet-50 layer set, He-normal with 1 % Laplace(0, 3 sigma) outliers.
     4: MobileNetV2 layer set, He-normal.
     5: 256 x [512,512,3,3]; a seeded fair coin per tensor picks N(0, sigma) or
        sigma * Student-t(3).  `n_tensors` truncates the list (same leading tensors).
+    6: InceptionV3-style layer set (factorised 1x7 / 7x1 / 1x3 / 3x1 and 5x5 kernels), He-normal.
     """
     if config == 1:
         shapes, dist = [(64, 64, 3, 3)], "normal"
@@ -174,6 +196,8 @@ def config_specs(config: int, seed: int = DEFAULT_SEED, n_tensors: int | None = 
         shapes, dist = mobilenetv2_shapes(), "normal"
     elif config == 5:
         shapes, dist = [(512, 512, 3, 3)] * 256, "coin"
+    elif config == 6:
+        shapes, dist = inceptionv3_shapes(), "normal"
     else:
         raise ValueError(f"unknown config {config}")
     if n_tensors is not None:

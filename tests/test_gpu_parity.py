@@ -155,7 +155,7 @@ def run_batched(sq, ws, bits, mode):
     return codes, scales
 
 
-@pytest.mark.parametrize("config,bits", [(2, 4), (3, 4), (3, 8), (4, 4)])
+@pytest.mark.parametrize("config,bits", [(2, 4), (3, 4), (3, 8), (4, 4), (6, 4)])
 def test_layer_sets_batched(sq, config, bits):
     specs = synth.config_specs(config)
     ws = [synth.generate(s) for s in specs]
