@@ -175,3 +175,69 @@ def test_small_kernels_in_a_layer_set(sq):
         for w, c, sc in zip(ws, codes, scales):
             want, want_s = oracle.quantize(w, bits, mode, threads=8)
             check(c, sc, want, want_s, f"{w.shape} bits={bits} mode={mode}")
+
+
+def random_values(rng, shape):
+    kind = rng.integers(0, 7)
+    if kind == 0:
+        w = rng.standard_normal(shape) * 0.05
+    elif kind == 1:
+        w = rng.standard_t(3, shape) * 0.05
+    elif kind == 2:                                   # few levels: ties, exact halves, zero sums
+        levels = int(rng.integers(2, 40))
+        w = rng.integers(-levels, levels + 1, shape) / float(rng.choice([2, 4, 8, 3, 5]))
+    elif kind == 3:                                   # one-sided perturbations
+        w = np.full(shape, 0.3) + rng.random(shape) * 0.1
+    elif kind == 4:                                   # mostly zeros
+        w = rng.standard_normal(shape) * (rng.random(shape) < 0.1)
+    elif kind == 5:                                   # a constant with a few outliers
+        w = np.full(shape, float(rng.choice([0.37, -1.25, 2.5])))
+        idx = rng.random(shape) < 0.02
+        w[idx] = rng.standard_normal(int(idx.sum())) * 3
+    else:                                             # huge dynamic range
+        w = rng.standard_normal(shape) * np.exp(rng.uniform(-20, 20, (shape[0], 1, 1, 1)))
+    w = w.astype(np.float32)
+    if shape[0] > 2 and rng.random() < 0.3:
+        w[int(rng.integers(0, shape[0]))] = 0.0
+    return w
+
+
+@pytest.mark.parametrize("block", range(8))
+def test_random_small_kernel_cases(sq, block):
+    """Seeded random cases on the shapes of this variant (cin * kh * kw a multiple of 4), value
+    patterns that reach the rare branches, every bit width and mode; each case is printed
+    before it runs."""
+    rng = np.random.default_rng(9000 + block)
+    kernels = [(1, 2), (2, 1), (1, 3), (3, 1), (2, 2), (1, 4), (1, 5), (5, 1), (1, 7), (7, 1), (5, 5)]
+    for case in range(40):
+        kh, kw = kernels[int(rng.integers(0, len(kernels)))]
+        K = kh * kw
+        step = 4 if K % 2 else (2 if K % 4 else 1)    # keeps cin * K a multiple of 4
+        hi = (8200 if K <= 4 else 4200 if K <= 7 else 1030) if rng.random() < 0.15 else 520
+        cin = step * int(rng.integers(1, hi // step + 1))
+        if K == 25 and cin > 1024:
+            cin = 1024                                 # beyond it the generic kernel's LDS limit decides
+        shape = (int(rng.integers(1, 5)), cin, kh, kw)
+        if cin * K > sq.squant_max_channel_elems(kh, kw) and cin % (8 if K <= 4 else 4):
+            continue                                   # too wide for the generic kernel, not a multiple for this one
+        w = random_values(rng, shape)
+        bits, mode = int(rng.integers(2, 9)), int(rng.integers(0, 4))
+        print(f"case block={block} #{case} shape={shape} bits={bits} mode={mode}", flush=True)
+        want, want_s = oracle.quantize(w, bits, mode, threads=4)
+        got, got_s = sq.squant_quantize(torch.from_numpy(w).cuda(), bits, mode)
+        torch.cuda.synchronize()
+        check(got, got_s, want, want_s, f"block={block} case={case} {shape} bits={bits} mode={mode}")
+        if case % 3 == 0:                              # again from 16-bit weights into another format
+            wtype = ["f16", "bf16"][int(rng.integers(0, 2))]
+            t16 = torch.from_numpy(w).to(torch.float16 if wtype == "f16" else torch.bfloat16)
+            w16 = oracle.widen(t16.view(torch.int16).numpy().view(np.uint16), wtype)
+            if not np.isfinite(w16).all():
+                continue
+            codes, scales = oracle.quantize(w16, bits, mode, threads=4)
+            fmt = "int4" if bits <= 4 else ["f32", "bf16"][int(rng.integers(0, 2))]
+            want = {"int4": oracle.pack_int4, "f32": lambda c: oracle.dequantize(c, scales),
+                    "bf16": lambda c: oracle.dequantize_bf16(c, scales)}[fmt](codes)
+            print(f"     again as {wtype} -> {fmt}", flush=True)
+            got, got_s = sq.squant_quantize_ex(t16.cuda(), bits, mode, sq.OUTPUTS[fmt])
+            torch.cuda.synchronize()
+            check(got, got_s, want, scales, f"{wtype}->{fmt} block={block} case={case} {shape} bits={bits} mode={mode}")
