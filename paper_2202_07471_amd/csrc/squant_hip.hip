@@ -121,8 +121,8 @@ Plan plan_tensor(const void* w, const void* out, int64_t N, int64_t K, int lds_l
       // LDS: the channel's int8 codes
       return Plan{variant, (int)round_up64(N / kpt), round_up((size_t)9 * N, 16)};
     }
-    case kK1x1: case kK1x2: case kK1x4: case kK1x8: {
-      const int nv = variant == kK1x1 ? 1 : variant == kK1x2 ? 2 : variant == kK1x4 ? 4 : 8;
+    case kK1x1: case kK1x2: case kK1x3: case kK1x4: case kK1x5: case kK1x6: case kK1x7: case kK1x8: {
+      const int nv = k1_variant_nv(variant);
       return Plan{variant, (int)round_up64((N / 4 + nv - 1) / nv), round_up((size_t)N, 16)};
     }
     case kDw9: return Plan{kDw9, kWave, 16};     // no LDS; 16 stands for "fits"
@@ -142,9 +142,10 @@ Plan plan_tensor(const void* w, const void* out, int64_t N, int64_t K, int lds_l
 }
 
 // Whether a tensor may join a launch of the mixed kernel: its variant is one the mixed kernel
-// carries (all but the eight-vector 1x1 variant) and fits its workgroup size and LDS.
+// carries (not the 1x1 variants of five to eight vectors per thread) and fits its workgroup
+// size and LDS.
 bool mixable(const Plan& p, size_t lds_cap) {
-  return p.variant != kK1x8 && p.variant != kK1Stream && !is_ks(p.variant) &&
+  return k1_variant_nv(p.variant) <= 4 && p.variant != kK1Stream && !is_ks(p.variant) &&
          p.threads <= kMixedMaxThreads &&
          p.lds <= lds_cap;
 }
@@ -230,7 +231,11 @@ int launch_part(const Group& g, size_t begin, size_t end, int qmax, int mode, in
   // (for one-element kernels E&K equals E and E&C equals E&K&C)
   static const kernel_t k1x1[4] = SQ_K1_ROW(256, 1);
   static const kernel_t k1x2[4] = SQ_K1_ROW(256, 2);
+  static const kernel_t k1x3[4] = SQ_K1_ROW(256, 3);
   static const kernel_t k1x4[4] = SQ_K1_ROW(256, 4);
+  static const kernel_t k1x5[4] = SQ_K1_ROW(256, 5);
+  static const kernel_t k1x6[4] = SQ_K1_ROW(256, 6);
+  static const kernel_t k1x7[4] = SQ_K1_ROW(256, 7);
   static const kernel_t k1x8[4] = SQ_K1_ROW(1024, 8);
   static const kernel_t k1x8_small[4] = SQ_K1_ROW(256, 8);
   static const kernel_t k1x8_mid[4] = SQ_K1_ROW(768, 8);
@@ -250,7 +255,11 @@ int launch_part(const Group& g, size_t begin, size_t end, int qmax, int mode, in
                           : (g.variant == kMixed || g.variant == kMixedWave) ? mixed[mode]
                           : g.variant == kK1x1 ? k1x1[mode]
                           : g.variant == kK1x2 ? k1x2[mode]
+                          : g.variant == kK1x3 ? k1x3[mode]
                           : g.variant == kK1x4 ? k1x4[mode]
+                          : g.variant == kK1x5 ? k1x5[mode]
+                          : g.variant == kK1x6 ? k1x6[mode]
+                          : g.variant == kK1x7 ? k1x7[mode]
                           : g.variant == kK1x8 ? (g.threads <= 256 ? k1x8_small[mode] : g.threads <= 768 ? k1x8_mid[mode] : k1x8[mode])
                           : g.variant == kK1Stream ? k1s[mode]
                           : g.variant == kDw9 ? dw9[mode]
@@ -606,6 +615,6 @@ const char* squant_status_string(int status) {
   }
 }
 
-int squant_version(void) { return 127; }
+int squant_version(void) { return 128; }
 
 }  // extern "C"

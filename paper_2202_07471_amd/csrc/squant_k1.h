@@ -335,9 +335,11 @@ __device__ __forceinline__ void k1_channel(const LaunchArgs& a, const TensorDesc
   emit_channel(code32, nvec, d.out, m, s, a.out_format, tid, T);
 }
 
-// The variants of up to 256 threads are compiled for eight waves per SIMD (64 VGPRs; the
-// unrolled per-element code otherwise spreads over ~95): measured 8-17 % faster from
-// cin = 1024 up, the extra waves hide the load latency.  The eight-vector variant is compiled
+// The variants of up to five vectors per thread are compiled for eight waves per SIMD (64
+// VGPRs; the unrolled per-element code otherwise spreads over ~95): measured 8-25 % faster
+// from cin = 1024 up, the extra waves hide the load latency.  Six vectors: six waves (5, 7
+// and 8 measured 9-21 % slower); seven: five waves (6 is 24 % slower, 8 spills massively).
+// The eight-vector variant is compiled
 // for five waves per SIMD in its 256-thread form (cin up to 8192; 4 and 6 were measured
 // slower), for six in its 768-thread form and keeps the 128 VGPRs that 16 waves per workgroup
 // allow in its 1024-thread form.  The steps matter because whole workgroups must fit: at
@@ -346,7 +348,7 @@ __device__ __forceinline__ void k1_channel(const LaunchArgs& a, const TensorDesc
 // there are 24 slots.
 template <int MAX_THREADS, int MODE, int NV>
 __global__ void __launch_bounds__(MAX_THREADS)
-    __attribute__((amdgpu_waves_per_eu(MAX_THREADS > 768 ? 4 : MAX_THREADS > 256 ? 6 : NV <= 4 ? 8 : 5))) squant_channel_k1(LaunchArgs a) {
+    __attribute__((amdgpu_waves_per_eu(MAX_THREADS > 768 ? 4 : MAX_THREADS > 256 ? 6 : NV <= 5 ? 8 : NV == 6 ? 6 : 5))) squant_channel_k1(LaunchArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];  // N bytes of biased codes
   __shared__ K9Shared sh;
   int m;

@@ -42,6 +42,7 @@ __global__ void __launch_bounds__(kMixedMaxThreads)
     const int nvec = d.N >> 2;
     if (nvec <= T) k1_channel<M1, 1>(a, d, m, smem, sh);
     else if (nvec <= 2 * T) k1_channel<M1, 2>(a, d, m, smem, sh);
+    else if (nvec <= 3 * T) k1_channel<M1, 3>(a, d, m, smem, sh);
     else k1_channel<M1, 4>(a, d, m, smem, sh);
   } else if (family == 3) {
     dw9_channels<MODE>(a, d, m);

@@ -16,6 +16,7 @@ enum Variant {
   kK1Stream = 8,                               // 1x1 / FC beyond kMaxK1Cin: weights walked repeatedly
   kDw9 = 9,                                    // depthwise 3x3 (cin per group = 1): one thread per channel
   kK1Team = 10,                                // 1x1 / FC up to kMaxTeamCin: 4 to 16 channels per wave
+  kK1x3 = 11, kK1x5 = 12, kK1x6 = 13, kK1x7 = 14,  // 1x1 / FC: 3, 5, 6, 7 vectors per thread
   kKs = 1024                                   // small kernels in registers: kKs + 4 * K + log2(kernels per thread)
 };
 
@@ -24,6 +25,19 @@ constexpr int kMaxK1Cin = 32768;  // 1x1 variant: cin % 4 == 0 up to here
 constexpr int kMaxTeamCin = 256;  // 1x1 channels this short share a wave
 
 SQ_HD int64_t round_up64(int64_t v) { return (v + 63) / 64 * 64; }
+
+// 16-byte vectors per thread of a 1x1 / FC variant (0: not one), and back.
+SQ_HD int k1_variant_nv(int variant) {
+  switch (variant) {
+    case kK1x1: return 1; case kK1x2: return 2; case kK1x3: return 3; case kK1x4: return 4;
+    case kK1x5: return 5; case kK1x6: return 6; case kK1x7: return 7; case kK1x8: return 8;
+    default: return 0;
+  }
+}
+SQ_HD int k1_variant_of(int nv) {
+  const int v[9] = {kGeneric, kK1x1, kK1x2, kK1x3, kK1x4, kK1x5, kK1x6, kK1x7, kK1x8};
+  return v[nv];
+}
 
 // Small kernels held in registers (squant_ks.h): the kernel sizes it is built for, and the
 // largest power of two (as its logarithm) of kernels one thread holds.
@@ -87,12 +101,22 @@ SQ_HD int choose_variant(int64_t N, int64_t K, bool aligned) {
     return best_c == 4 ? kK9x4 : best_c == 2 ? kK9x2 : kK9x1;
   }
   if (family == 1) {
-    // 16-byte vectors per thread: one full wave per channel while that takes at most four
-    // per thread, then up to 256 threads with four, then eight (measured: spreading a
-    // channel over more threads sooner is up to 1.6x slower, the workgroup-wide steps of
-    // the channel stage then run in more waves)
+    // 16-byte vectors per thread, NV, with T = round_up64(ceil(nvec / NV)) threads: up to four
+    // while that needs at most 256 threads, else five to eight (measured: spreading a channel
+    // over more threads sooner is up to 1.6x slower, the workgroup-wide steps of the channel
+    // stage then run in more waves); within the class the count that leaves the fewest
+    // thread-vector slots NV * T idle, the larger one on ties.  Beyond 256 threads only eight.
     const int64_t nvec = N / 4;
-    return nvec <= 64 ? kK1x1 : nvec <= 128 ? kK1x2 : nvec <= 1024 ? kK1x4 : kK1x8;
+    if (nvec > 2048) return kK1x8;
+    const int lo = nvec <= 1024 ? 1 : 5, hi = nvec <= 1024 ? 4 : 8;
+    int best = hi;
+    int64_t best_slots = INT64_MAX;
+    for (int nv = hi; nv >= lo; --nv) {
+      const int64_t th = round_up64((nvec + nv - 1) / nv);
+      if (th > 256) continue;
+      if (nv * th < best_slots) { best_slots = nv * th; best = nv; }
+    }
+    return k1_variant_of(best);
   }
   if (family == 2) return kK1Stream;
   if (family == 3) return kDw9;

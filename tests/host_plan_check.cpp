@@ -33,11 +33,20 @@ int main() {
           }
         } else if (family == 1) {
           ++k1;
-          const int nv = v == kK1x1 ? 1 : v == kK1x2 ? 2 : v == kK1x4 ? 4 : v == kK1x8 ? 8 : 0;
+          const int nv = k1_variant_nv(v);
           if (nv == 0 || K != 1 || !aligned || N % 4 || N > kMaxK1Cin || N <= kMaxTeamCin) { ++bad; continue; }
           const int64_t nvec = N / 4, threads = round_up64((nvec + nv - 1) / nv);
           bad += threads * nv < nvec;
           bad += threads > (nv == 8 ? 1024 : 256);
+          bad += k1_variant_of(nv) != v;
+          // up to four vectors per thread while 256 threads suffice for that, else five to eight;
+          // no admissible count of the class leaves fewer thread-vector slots idle
+          bad += (nvec <= 1024) != (nv <= 4);
+          for (int c = (nv <= 4 ? 1 : 5); c <= (nv <= 4 ? 4 : 8) && nvec <= 2048; ++c) {
+            const int64_t th = round_up64((nvec + c - 1) / c);
+            if (th > 256) continue;
+            bad += c * th < nv * threads;
+          }
         } else if (family == 3) {
           bad += v != kDw9 || K != 9 || N != 1;
           bad += work_items(130, N, K, 64, family) != 3 || work_items(128, N, K, 64, family) != 2;
