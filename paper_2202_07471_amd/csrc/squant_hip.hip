@@ -615,6 +615,6 @@ const char* squant_status_string(int status) {
   }
 }
 
-int squant_version(void) { return 128; }
+int squant_version(void) { return 129; }
 
 }  // extern "C"

@@ -45,11 +45,12 @@ constexpr int kKsMaxK = 25;
 SQ_HD bool ks_has(int64_t K) { return K == 2 || K == 3 || K == 4 || K == 5 || K == 7 || K == 25; }
 SQ_HD constexpr int ks_max_kpt_log2(int64_t K) { return K <= 4 ? 3 : K <= 7 ? 2 : 0; }
 // log2 of the kernels per thread for a channel of N such kernels: the largest power of two that
-// divides N and leaves the waves at least 60 % full, else the one that keeps them fullest
-// (measured: fewer, longer threads win down to that fill: 1x7 with cin 192 and 1x3 with cin 384
-// 10 % faster at 75 % than at 100 %, 1x7 with cin 160 13 % faster at 62 % than at 83 %, cin 128
-// 50 % slower at 50 % than at 100 %); only the largest one is built for workgroups beyond
-// 256 threads.  -1: none fits (then the generic kernel takes the tensor).
+// divides N and puts the channel into ONE wave at least 60 % full, else the one that keeps the
+// waves fullest (measured: a one-wave workgroup wins down to that fill - 1x7 with cin 192 and
+// 1x3 with cin 384 10 % faster at 75 % than three full waves, 1x7 with cin 160 13 % faster at
+// 62 % than at 83 %, cin 128 50 % slower at 50 % than at 100 % - while among workgroups of
+// several waves the fullest wins by 11-13 %); only the largest one is built for workgroups
+// beyond 256 threads.  -1: none fits (then the generic kernel takes the tensor).
 SQ_HD int ks_kpt_log2(int64_t N, int64_t K) {
   if (!ks_has(K) || ((N * K) & 3) != 0) return -1;
   const int top = ks_max_kpt_log2(K);
@@ -60,7 +61,7 @@ SQ_HD int ks_kpt_log2(int64_t N, int64_t K) {
     if (N % c != 0) continue;
     const int64_t th = round_up64(N / c);
     if (th > 1024 || (th > 256 && lg != top)) continue;
-    if ((N / c) * 10 >= th * 6) return lg;
+    if (th == 64 && (N / c) * 10 >= th * 6) return lg;
     if ((N / c) * best_den > best_num * th) { best_num = N / c; best_den = th; best = lg; }
   }
   return best;
@@ -88,7 +89,9 @@ SQ_HD int choose_family(int64_t N, int64_t K, bool aligned) {
 SQ_HD int choose_variant(int64_t N, int64_t K, bool aligned) {
   const int family = choose_family(N, K, aligned);
   if (family == 9) {
-    // kernels per thread: the largest of 4, 2, 1 that keeps the waves fullest
+    // kernels per thread: four when that puts the channel into one wave at least 60 % full
+    // (cin 152..256; measured 11 % faster than three full waves at cin 160 and 192), else the
+    // largest of 4, 2, 1 that keeps the waves fullest
     // (fill = (N / c) / round_up64(N / c), compared by cross-multiplication)
     int best_c = 4;
     int64_t best_num = 0, best_den = 1;
@@ -96,6 +99,7 @@ SQ_HD int choose_variant(int64_t N, int64_t K, bool aligned) {
       const int64_t th = round_up64(N / c);
       if (th > 256 && c != 4) continue;
       const int64_t num = N / c;
+      if (th == 64 && num * 10 >= th * 6) { best_c = c; break; }
       if (num * best_den > best_num * th) { best_num = num; best_den = th; best_c = c; }
     }
     return best_c == 4 ? kK9x4 : best_c == 2 ? kK9x2 : kK9x1;

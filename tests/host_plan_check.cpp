@@ -25,11 +25,16 @@ int main() {
           bad += threads * kpt < N;          // all kernels covered
           bad += threads > 1024;
           bad += kpt != 4 && threads > 256;  // the narrow variants are built for 256 threads
-          // no other admissible choice keeps the waves fuller
-          for (int c : {1, 2, 4}) {
-            const int64_t th = round_up64(N / c);
-            if (th > 256 && c != 4) continue;
-            bad += (N / c) * threads > (N / kpt) * th;
+          // one wave at least 60 % full with four kernels per thread, else no other admissible
+          // choice keeps the waves fuller
+          if (round_up64(N / 4) == 64 && (N / 4) * 10 >= 64 * 6) {
+            bad += kpt != 4;
+          } else {
+            for (int c : {1, 2, 4}) {
+              const int64_t th = round_up64(N / c);
+              if (th > 256 && c != 4) continue;
+              bad += (N / c) * threads > (N / kpt) * th;
+            }
           }
         } else if (family == 1) {
           ++k1;
@@ -71,12 +76,12 @@ int main() {
           bad += threads * kpt < N || threads > 1024;
           bad += kpt != top && threads > 256;  // only the largest is built for 1024 threads
           bad += K * kpt > 32 && kpt > 1;      // elements a thread holds in registers
-          bool roomy = false;                  // some admissible choice leaves the waves 60 % full
+          bool roomy = false;                  // some admissible choice is one wave at least 60 % full
           for (int c = 1; c <= top; c *= 2) {
             if (N % c) continue;
             const int64_t th = round_up64(N / c);
             if (th > 1024 || (th > 256 && c != top)) continue;
-            const bool ok60 = (N / c) * 10 >= th * 6;
+            const bool ok60 = th == 64 && (N / c) * 10 >= th * 6;
             roomy |= ok60;
             bad += ok60 && c > kpt;            // the largest such count is the one taken
           }
