@@ -368,3 +368,17 @@ def test_oversize_channel_is_an_error(sq):
     with pytest.raises(sq.SQuantError) as e:
         sq.squant_quantize(w, 4, 2)
     assert e.value.status == 7
+
+
+# ---------------------------------------------------------------------------
+# 1x1 / FC widths that take each number of 16-byte vectors per thread (1..8), with full and
+# ragged last rounds
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("kind", ["normal", "heavy", "grid"])
+@pytest.mark.parametrize("cin", [260, 300, 576, 768, 772, 1280, 1536, 1600, 2560, 4100, 4608, 5120, 5376, 6656,
+                                 7168, 7172, 8188])
+def test_fc_widths_for_every_vector_count(sq, cin, kind):
+    w = rand_weights((3, cin, 1, 1), 900 + cin, kind)
+    for bits, mode in ((4, 2), (8, 2), (3, 0)):
+        codes, scales = run_single(sq, w, bits, mode)
+        assert_same(codes, scales, w, bits, mode, what=f"cin={cin} {kind} bits={bits} mode={mode}")
