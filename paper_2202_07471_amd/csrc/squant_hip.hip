@@ -108,7 +108,10 @@ struct Group {
   bool fixed_threads = false;  // mixed launch: a non-generic member has set the workgroup size
 };
 
-struct Plan { int variant; int threads; size_t lds; };
+// threads / lds: of a launch of the tensor's own variant.  mix_threads: what the tensor needs as
+// a member of a mixed launch (0: it cannot join one), where the per-thread work follows the
+// launch's workgroup size.
+struct Plan { int variant; int threads; size_t lds; int mix_threads; };
 
 inline size_t round_up(size_t v, size_t to) { return (v + to - 1) / to * to; }
 
@@ -119,34 +122,38 @@ Plan plan_tensor(const void* w, const void* out, int64_t N, int64_t K, int lds_l
     case kK9x1: case kK9x2: case kK9x4: {
       const int kpt = variant == kK9x4 ? 4 : variant == kK9x2 ? 2 : 1;
       // LDS: the channel's int8 codes
-      return Plan{variant, (int)round_up64(N / kpt), round_up((size_t)9 * N, 16)};
+      const int th = (int)round_up64(N / kpt);
+      return Plan{variant, th, round_up((size_t)9 * N, 16), th};
     }
     case kK1x1: case kK1x2: case kK1x3: case kK1x4: case kK1x5: case kK1x6: case kK1x7: case kK1x8: {
       const int nv = k1_variant_nv(variant);
-      return Plan{variant, (int)round_up64((N / 4 + nv - 1) / nv), round_up((size_t)N, 16)};
+      const int64_t nvec = N / 4;
+      const int th = (int)round_up64((nvec + nv - 1) / nv);
+      // the mixed kernel carries the routines of up to four vectors per thread
+      const int mix = nv <= 4 ? th : nvec <= 4 * kMixedMaxThreads ? (int)round_up64((nvec + 3) / 4) : 0;
+      return Plan{variant, th, round_up((size_t)N, 16), mix};
     }
-    case kDw9: return Plan{kDw9, kWave, 16};     // no LDS; 16 stands for "fits"
-    case kK1Team: return Plan{kK1Team, kWave, 16};
+    case kDw9: return Plan{kDw9, kWave, 16, kWave};     // no LDS; 16 stands for "fits"
+    case kK1Team: return Plan{kK1Team, kWave, 16, kWave};
     case kK1Stream: {
       const size_t lds = round_up((size_t)N, 16);  // the channel's int8 codes
-      if (lds + sizeof(K9Shared) + 64 > (size_t)lds_limit) return Plan{kK1Stream, 0, 0};
-      return Plan{kK1Stream, 1024, lds};
+      if (lds + sizeof(K9Shared) + 64 > (size_t)lds_limit) return Plan{kK1Stream, 0, 0, 0};
+      return Plan{kK1Stream, 1024, lds, 0};
     }
     default: break;
   }
   if (is_ks(variant))  // LDS: the channel's int8 codes
-    return Plan{variant, (int)round_up64(N / ks_variant_kpt(variant)), round_up((size_t)K * N, 16)};
+    return Plan{variant, (int)round_up64(N / ks_variant_kpt(variant)), round_up((size_t)K * N, 16), 0};
   const size_t lds = generic_lds_bytes(N, K);
-  if (lds + kStaticLds > (size_t)lds_limit) return Plan{kGeneric, 0, 0};
-  return Plan{kGeneric, generic_threads(N, K), lds};
+  if (lds + kStaticLds > (size_t)lds_limit) return Plan{kGeneric, 0, 0, 0};
+  const int th = generic_threads(N, K);
+  return Plan{kGeneric, th, lds, th};
 }
 
-// Whether a tensor may join a launch of the mixed kernel: its variant is one the mixed kernel
-// carries (not the 1x1 variants of five to eight vectors per thread) and fits its workgroup
-// size and LDS.
+// Whether a tensor may join a launch of the mixed kernel: the mixed kernel carries a routine
+// for it that fits its workgroup size and LDS.
 bool mixable(const Plan& p, size_t lds_cap) {
-  return k1_variant_nv(p.variant) <= 4 && p.variant != kK1Stream && !is_ks(p.variant) &&
-         p.threads <= kMixedMaxThreads &&
+  return p.mix_threads > 0 && p.mix_threads <= kMixedMaxThreads &&
          p.lds <= lds_cap;
 }
 
@@ -423,7 +430,7 @@ int squant_quantize_batched_ex(const squant_tensor_t* h_tensors, int32_t n_tenso
   int widest = 0;
   for (int32_t i = 0; i < n_tensors; ++i) {
     const Plan& p = plans[(size_t)i];
-    if (use_mixed && mixable(p, lds_cap) && p.variant != kGeneric) widest = std::max(widest, p.threads);
+    if (use_mixed && mixable(p, lds_cap) && p.variant != kGeneric) widest = std::max(widest, p.mix_threads);
   }
   const bool two_classes = widest > 2 * kWave;
   std::vector<Group> groups;
@@ -432,14 +439,15 @@ int squant_quantize_batched_ex(const squant_tensor_t* h_tensors, int32_t n_tenso
     const Plan& p = plans[(size_t)i];
     const bool in_ks_mixed = use_ks_mixed && is_ks(p.variant) && p.threads <= kKsMixedMaxThreads;
     const bool in_mixed = in_ks_mixed || (use_mixed && mixable(p, lds_cap));
-    const int mixed_kind = in_ks_mixed ? kKsMixed : (two_classes && p.threads <= kWave) ? kMixedWave : kMixed;
+    const int need_threads = in_ks_mixed ? p.threads : p.mix_threads;
+    const int mixed_kind = in_ks_mixed ? kKsMixed : (two_classes && need_threads <= kWave) ? kMixedWave : kMixed;
     Group* g = nullptr;
     for (auto& c : groups) {
       if (in_mixed ? c.variant == mixed_kind
                    : (c.variant == p.variant && c.threads == p.threads && c.lds == p.lds)) { g = &c; break; }
     }
     if (!g) {
-      groups.push_back(Group{in_mixed ? mixed_kind : p.variant, p.threads, p.lds, {}});
+      groups.push_back(Group{in_mixed ? mixed_kind : p.variant, in_mixed ? need_threads : p.threads, p.lds, {}});
       g = &groups.back();
     }
     if (in_mixed) {
@@ -447,10 +455,10 @@ int squant_quantize_batched_ex(const squant_tensor_t* h_tensors, int32_t n_tenso
       // depend on it); the generic routine strides by whatever size it is given, so a generic
       // member only sets the size of a launch that has no other kind of member
       if (p.variant != kGeneric) {
-        g->threads = g->fixed_threads ? std::max(g->threads, p.threads) : p.threads;
+        g->threads = g->fixed_threads ? std::max(g->threads, need_threads) : need_threads;
         g->fixed_threads = true;
       } else if (!g->fixed_threads) {
-        g->threads = std::max(g->threads, p.threads);
+        g->threads = std::max(g->threads, need_threads);
       }
       g->lds = std::max(g->lds, p.lds);
     }
@@ -615,6 +623,6 @@ const char* squant_status_string(int status) {
   }
 }
 
-int squant_version(void) { return 129; }
+int squant_version(void) { return 130; }
 
 }  // extern "C"

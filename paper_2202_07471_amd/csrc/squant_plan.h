@@ -105,13 +105,17 @@ SQ_HD int choose_variant(int64_t N, int64_t K, bool aligned) {
     return best_c == 4 ? kK9x4 : best_c == 2 ? kK9x2 : kK9x1;
   }
   if (family == 1) {
-    // 16-byte vectors per thread, NV, with T = round_up64(ceil(nvec / NV)) threads: up to four
+    // 16-byte vectors per thread, NV, with T = round_up64(ceil(nvec / NV)) threads: one wave
+    // while that takes at most seven per thread (below); else up to four
     // while that needs at most 256 threads, else five to eight (measured: spreading a channel
     // over more threads sooner is up to 1.6x slower, the workgroup-wide steps of the channel
     // stage then run in more waves); within the class the count that leaves the fewest
     // thread-vector slots NV * T idle, the larger one on ties.  Beyond 256 threads only eight.
     const int64_t nvec = N / 4;
     if (nvec > 2048) return kK1x8;
+    // one wave per channel up to seven vectors per thread (cin 1028..1792: measured 5-37 %
+    // faster than two waves of three or four; eight in one wave is 9 % slower than two of four)
+    if (nvec > 256 && nvec <= 448) return k1_variant_of((int)((nvec + 63) / 64));
     const int lo = nvec <= 1024 ? 1 : 5, hi = nvec <= 1024 ? 4 : 8;
     int best = hi;
     int64_t best_slots = INT64_MAX;

@@ -46,6 +46,10 @@ int main() {
           bad += k1_variant_of(nv) != v;
           // up to four vectors per thread while 256 threads suffice for that, else five to eight;
           // no admissible count of the class leaves fewer thread-vector slots idle
+          if (nvec > 256 && nvec <= 448) {  // one wave of five to seven vectors per thread
+            bad += nv != (nvec + 63) / 64 || threads != 64;
+            continue;
+          }
           bad += (nvec <= 1024) != (nv <= 4);
           for (int c = (nv <= 4 ? 1 : 5); c <= (nv <= 4 ? 4 : 8) && nvec <= 2048; ++c) {
             const int64_t th = round_up64((nvec + c - 1) / c);
