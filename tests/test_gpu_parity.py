@@ -382,3 +382,11 @@ def test_fc_widths_for_every_vector_count(sq, cin, kind):
     for bits, mode in ((4, 2), (8, 2), (3, 0)):
         codes, scales = run_single(sq, w, bits, mode)
         assert_same(codes, scales, w, bits, mode, what=f"cin={cin} {kind} bits={bits} mode={mode}")
+
+
+def test_many_output_channels(sq):
+    """A vocabulary-sized FC layer and a wide 1x3 layer: tens of thousands of workgroups per tensor."""
+    for shape in ((50257, 768, 1, 1), (30000, 96, 1, 3)):
+        w = rand_weights(shape, 61, "normal")
+        codes, scales = run_single(sq, w, 4, 2)
+        assert_same(codes, scales, w, 4, 2, threads=16, what=f"{shape}")
