@@ -68,10 +68,11 @@ def test_many_layers_in_one_call(sq):
         assert same_range(r, oracle.activation_range(g, b, 6.0, relu, 8))
 
 
-def test_whole_network_call(sq):
-    """ResNet-18 shaped weights, a batch norm after every layer but the last: the one call
-    gives what the weight solver and the range kernel give separately, i.e. the reference."""
-    specs = synth.config_specs(2)
+@pytest.mark.parametrize("config", [2, 6])
+def test_whole_network_call(sq, config):
+    """ResNet-18 / InceptionV3-style weights, a batch norm after every layer but the last: the one
+    call gives what the weight solver and the range kernel give separately, i.e. the reference."""
+    specs = synth.config_specs(config)
     rng = np.random.default_rng(11)
     layers, host = [], []
     for i, s in enumerate(specs):
