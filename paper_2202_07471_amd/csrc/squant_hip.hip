@@ -623,6 +623,6 @@ const char* squant_status_string(int status) {
   }
 }
 
-int squant_version(void) { return 130; }
+int squant_version(void) { return 131; }
 
 }  // extern "C"
