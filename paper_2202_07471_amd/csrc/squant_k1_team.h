@@ -185,8 +185,10 @@ __device__ __forceinline__ void k1_team_dispatch(const LaunchArgs& a, const Tens
   else k1_team_channels<MODE, 16, 4>(a, d, item);
 }
 
+// Compiled for eight waves per SIMD (64 VGPRs instead of 66: measured 1-4 % faster).
 template <int MODE>
-__global__ void __launch_bounds__(256) squant_channel_k1_team(LaunchArgs a) {
+__global__ void __launch_bounds__(256)
+    __attribute__((amdgpu_waves_per_eu(8))) squant_channel_k1_team(LaunchArgs a) {
   int m;
   const TensorDesc d = locate(a, blockIdx.x, m);
   k1_team_dispatch<MODE>(a, d, m);
