@@ -128,7 +128,7 @@ Plan plan_tensor(const void* w, const void* out, int64_t N, int64_t K, int lds_l
     case kK1x1: case kK1x2: case kK1x3: case kK1x4: case kK1x5: case kK1x6: case kK1x7: case kK1x8: {
       const int nv = k1_variant_nv(variant);
       const int64_t nvec = N / 4;
-      const int th = (int)round_up64((nvec + nv - 1) / nv);
+      const int th = (int)k1_threads(nvec, nv);
       // the mixed kernel carries the routines of up to four vectors per thread
       const int mix = nv <= 4 ? th : nvec <= 4 * kMixedMaxThreads ? (int)round_up64((nvec + 3) / 4) : 0;
       return Plan{variant, th, round_up((size_t)N, 16), mix};
@@ -246,6 +246,8 @@ int launch_part(const Group& g, size_t begin, size_t end, int qmax, int mode, in
   static const kernel_t k1x8[4] = SQ_K1_ROW(1024, 8);
   static const kernel_t k1x8_small[4] = SQ_K1_ROW(256, 8);
   static const kernel_t k1x8_mid[4] = SQ_K1_ROW(768, 8);
+  static const kernel_t k1x5_mid[4] = SQ_K1_ROW(768, 5);
+  static const kernel_t k1x6_mid[4] = SQ_K1_ROW(768, 6);
 #undef SQ_K1_ROW
   static const kernel_t k1s[4] = {squant_channel_k1_stream<SQUANT_MODE_E>, squant_channel_k1_stream<SQUANT_MODE_E>,
                                   squant_channel_k1_stream<SQUANT_MODE_EKC>, squant_channel_k1_stream<SQUANT_MODE_EKC>};
@@ -264,8 +266,8 @@ int launch_part(const Group& g, size_t begin, size_t end, int qmax, int mode, in
                           : g.variant == kK1x2 ? k1x2[mode]
                           : g.variant == kK1x3 ? k1x3[mode]
                           : g.variant == kK1x4 ? k1x4[mode]
-                          : g.variant == kK1x5 ? k1x5[mode]
-                          : g.variant == kK1x6 ? k1x6[mode]
+                          : g.variant == kK1x5 ? (g.threads <= 256 ? k1x5[mode] : k1x5_mid[mode])
+                          : g.variant == kK1x6 ? (g.threads <= 256 ? k1x6[mode] : k1x6_mid[mode])
                           : g.variant == kK1x7 ? k1x7[mode]
                           : g.variant == kK1x8 ? (g.threads <= 256 ? k1x8_small[mode] : g.threads <= 768 ? k1x8_mid[mode] : k1x8[mode])
                           : g.variant == kK1Stream ? k1s[mode]
@@ -623,6 +625,6 @@ const char* squant_status_string(int status) {
   }
 }
 
-int squant_version(void) { return 131; }
+int squant_version(void) { return 132; }
 
 }  // extern "C"

@@ -26,6 +26,22 @@ constexpr int kMaxTeamCin = 256;  // 1x1 channels this short share a wave
 
 SQ_HD int64_t round_up64(int64_t v) { return (v + 63) / 64 * 64; }
 
+// Workgroup size for a 1x1 / FC channel of more than 1024 vectors in whole multiples of four
+// waves, so that the waves of a workgroup spread evenly over the four SIMDs of a compute unit,
+// and the vectors per thread that go with it.
+SQ_HD int64_t k1_wide_threads(int64_t nvec) {
+  return nvec <= 2048 ? 256 : nvec <= 4096 ? 512 : nvec <= 6144 ? 768 : 1024;
+}
+SQ_HD int k1_wide_nv(int64_t nvec) {
+  const int64_t T = k1_wide_threads(nvec);
+  return (int)((nvec + T - 1) / T);
+}
+// Threads a 1x1 / FC channel of nvec vectors takes with nv vectors per thread.
+SQ_HD int64_t k1_threads(int64_t nvec, int nv) {
+  if (nvec > 1024 && nv <= 6 && k1_wide_nv(nvec) == nv) return k1_wide_threads(nvec);
+  return round_up64((nvec + nv - 1) / nv);
+}
+
 // 16-byte vectors per thread of a 1x1 / FC variant (0: not one), and back.
 SQ_HD int k1_variant_nv(int variant) {
   switch (variant) {
@@ -112,6 +128,10 @@ SQ_HD int choose_variant(int64_t N, int64_t K, bool aligned) {
     // stage then run in more waves); within the class the count that leaves the fewest
     // thread-vector slots NV * T idle, the larger one on ties.  Beyond 256 threads only eight.
     const int64_t nvec = N / 4;
+    // wide channels: five or six vectors per thread in workgroups of 256, 512 or 768 threads
+    // where that covers the channel (measured 11-23 % faster than eight vectors in a workgroup
+    // of 5-7 or 9-11 waves at cin 6144, 9216-12288, 18432; with seven the gain is lost to spills)
+    if (nvec > 1024 && k1_wide_nv(nvec) <= 6) return k1_variant_of(k1_wide_nv(nvec));
     if (nvec > 2048) return kK1x8;
     // one wave per channel up to seven vectors per thread (cin 1028..1792: measured 5-37 %
     // faster than two waves of three or four; eight in one wave is 9 % slower than two of four)

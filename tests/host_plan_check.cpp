@@ -40,10 +40,15 @@ int main() {
           ++k1;
           const int nv = k1_variant_nv(v);
           if (nv == 0 || K != 1 || !aligned || N % 4 || N > kMaxK1Cin || N <= kMaxTeamCin) { ++bad; continue; }
-          const int64_t nvec = N / 4, threads = round_up64((nvec + nv - 1) / nv);
+          const int64_t nvec = N / 4, threads = k1_threads(nvec, nv);
           bad += threads * nv < nvec;
-          bad += threads > (nv == 8 ? 1024 : 256);
+          bad += threads % 64 != 0 || threads > (nv == 8 ? 1024 : nv >= 5 && nv <= 6 ? 768 : 256);
           bad += k1_variant_of(nv) != v;
+          if (nvec > 1024 && k1_wide_nv(nvec) <= 6) {
+            // wide channels: five or six vectors per thread in 256, 512 or 768 threads
+            bad += nv != k1_wide_nv(nvec) || nv < 5 || threads != k1_wide_threads(nvec) || threads % 256 != 0;
+            continue;
+          }
           // up to four vectors per thread while 256 threads suffice for that, else five to eight;
           // no admissible count of the class leaves fewer thread-vector slots idle
           if (nvec > 256 && nvec <= 448) {  // one wave of five to seven vectors per thread
