@@ -625,6 +625,6 @@ const char* squant_status_string(int status) {
   }
 }
 
-int squant_version(void) { return 132; }
+int squant_version(void) { return 133; }
 
 }  // extern "C"

@@ -122,7 +122,8 @@ SQ_HD int choose_variant(int64_t N, int64_t K, bool aligned) {
   }
   if (family == 1) {
     // 16-byte vectors per thread, NV, with T = round_up64(ceil(nvec / NV)) threads: one wave
-    // while that takes at most seven per thread (below); else up to four
+    // while that takes at most seven per thread (below); else up to five (five where it fills
+    // the lanes better than four: cin 2560 32 %, cin 3584 17 % faster)
     // while that needs at most 256 threads, else five to eight (measured: spreading a channel
     // over more threads sooner is up to 1.6x slower, the workgroup-wide steps of the channel
     // stage then run in more waves); within the class the count that leaves the fewest
@@ -136,7 +137,7 @@ SQ_HD int choose_variant(int64_t N, int64_t K, bool aligned) {
     // one wave per channel up to seven vectors per thread (cin 1028..1792: measured 5-37 %
     // faster than two waves of three or four; eight in one wave is 9 % slower than two of four)
     if (nvec > 256 && nvec <= 448) return k1_variant_of((int)((nvec + 63) / 64));
-    const int lo = nvec <= 1024 ? 1 : 5, hi = nvec <= 1024 ? 4 : 8;
+    const int lo = nvec <= 1024 ? 1 : 5, hi = nvec <= 1024 ? 5 : 8;
     int best = hi;
     int64_t best_slots = INT64_MAX;
     for (int nv = hi; nv >= lo; --nv) {

@@ -49,14 +49,14 @@ int main() {
             bad += nv != k1_wide_nv(nvec) || nv < 5 || threads != k1_wide_threads(nvec) || threads % 256 != 0;
             continue;
           }
-          // up to four vectors per thread while 256 threads suffice for that, else five to eight;
+          // up to five vectors per thread while 256 threads suffice for that, else five to eight;
           // no admissible count of the class leaves fewer thread-vector slots idle
           if (nvec > 256 && nvec <= 448) {  // one wave of five to seven vectors per thread
             bad += nv != (nvec + 63) / 64 || threads != 64;
             continue;
           }
-          bad += (nvec <= 1024) != (nv <= 4);
-          for (int c = (nv <= 4 ? 1 : 5); c <= (nv <= 4 ? 4 : 8) && nvec <= 2048; ++c) {
+          bad += nvec <= 1024 ? nv > 5 : nv < 5;
+          for (int c = (nvec <= 1024 ? 1 : 5); c <= (nvec <= 1024 ? 5 : 8) && nvec <= 2048; ++c) {
             const int64_t th = round_up64((nvec + c - 1) / c);
             if (th > 256) continue;
             bad += c * th < nv * threads;
