@@ -245,3 +245,131 @@ def test_tie_order_in_large_groups(shape):
                         assert n > last_tied
                         tie_seen += 1
     assert tie_seen > 0
+
+
+# ---- mode E&C (Section 4.3 ablation: SQuant-C straight after rounding) ----
+#
+# Reading pinned here: the kernel stage flips nothing, the perturbation update of Algorithm 3
+# is taken with k = 0, i.e. every kernel offers its largest-|p| element among those with the
+# sign of the kernel's own sum (either sign when that sum is exactly 0), and SQuant-C then
+# ranks the kernels whose candidate has the sign of the channel sum.  A channel can run out of
+# such kernels; Eq. (7) is then missed by whole steps and the test says by how many.
+
+def ec_candidate_without_sorting(P):
+    """P: [K] Q23 perturbations of one rounded kernel -> (index, value) or (-1, 0)."""
+    e = int(P.astype(np.int64).sum())
+    mags = np.abs(P.astype(np.int64))
+    if e != 0:
+        mags = np.where(np.sign(P) == np.sign(e), mags, 0)
+    if mags.max() == 0:
+        return -1, 0
+    i = int(np.flatnonzero(mags == mags.max())[0])      # lowest index among the largest
+    return i, int(P[i])
+
+
+def test_mode_ec_hand_example():
+    """Two 1x3 kernels, scale exactly 1 (one element equals qmax = 7 at 4 bits).
+    kernel 0: x = (7, .4, .3)    -> codes (7,0,0), p = (0, -.4, -.3),   sum -.7
+    kernel 1: x = (.45, .2, -.1) -> codes (0,0,0), p = (-.45, -.2, +.1), sum -.55
+    channel sum -1.25 -> one flip towards +; candidates are -.4 (kernel 0, index 1) and -.45
+    (kernel 1, index 0); the larger one flips: kernel 1 element 0 goes from 0 to 1."""
+    w = np.array([[[7.0, 0.4, 0.3], [0.45, 0.2, -0.1]]], np.float32).reshape(1, 2, 1, 3)
+    codes, scales, tr = oracle.quantize_trace(w, 4, oracle.MODE_EC)
+    assert scales[0] == np.float32(1.0)
+    assert tr["kernel_k"].tolist() == [[0, 0]]
+    assert tr["cand_index"].tolist() == [[1, 0]]
+    assert tr["cand_value"][0, 0] == -int(round(float(np.float32(0.4)) * ONE))
+    assert tr["cand_value"][0, 1] == -int(round(float(np.float32(0.45)) * ONE))
+    assert int(tr["channel_k"][0]) == 1
+    assert codes.reshape(2, 3).tolist() == [[7, 0, 0], [1, 0, 0]]
+    # with the kernel stage in between the answer is another one: kernel 0 (-.7) and kernel 1
+    # (-.55) each flip their largest element, the channel sum becomes +.75 and SQuant-C takes
+    # back the flip whose post-flip perturbation is larger (+.6 in kernel 0 against +.55)
+    codes_ekc, _ = oracle.quantize(w, 4, MODE_EKC)
+    assert codes_ekc.reshape(2, 3).tolist() == [[7, 0, 0], [1, 0, 0]]
+    codes_ek, _ = oracle.quantize(w, 4, MODE_EK)
+    assert codes_ek.reshape(2, 3).tolist() == [[7, 1, 0], [1, 0, 0]]
+
+
+@pytest.mark.parametrize("kind", ["normal", "heavy", "grid"])
+@pytest.mark.parametrize("shape", [(40, 12, 3, 3), (30, 7, 2, 2), (30, 12, 1, 3), (20, 9, 1, 5)])
+def test_mode_ec_candidates_and_restricted_optimum(kind, shape):
+    rng = np.random.default_rng(seed_of("ec", kind, shape))
+    w = make_weights(rng, shape, kind)
+    M, N, kh, kw = shape
+    K = kh * kw
+    ce, _, te = oracle.quantize_trace(w, 4, MODE_E)
+    cc, _, tc = oracle.quantize_trace(w, 4, oracle.MODE_EC)
+    ce = ce.reshape(M, N, K).astype(int)
+    cc = cc.reshape(M, N, K).astype(int)
+    P0 = te["perturbation"]
+    # no kernel-stage flip: the perturbations SQuant-C sees are those of plain rounding
+    assert (tc["kernel_k"] == 0).all()
+    assert (tc["perturbation"] == P0).all()
+    assert (tc["kernel_sum"].astype(np.int64) == P0.astype(np.int64).sum(-1)).all()
+    seen = {"same": 0, "zero": 0, "none": 0, "short": 0, "flipped": 0}
+    for m in range(M):
+        for n in range(N):
+            want_i, want_v = ec_candidate_without_sorting(P0[m, n])
+            assert int(tc["cand_index"][m, n]) == want_i
+            assert int(tc["cand_value"][m, n]) == want_v
+            e = int(P0[m, n].astype(np.int64).sum())
+            seen["none" if want_i < 0 else ("zero" if e == 0 else "same")] += 1
+        EC = int(P0[m].astype(np.int64).sum())
+        assert EC == int(tc["channel_sum"][m])
+        V, idx = tc["cand_value"][m], tc["cand_index"][m]
+        changed = np.argwhere(ce[m] != cc[m])
+        S = []
+        for n, i in changed:
+            assert i == idx[n]
+            assert cc[m, n, i] - ce[m, n, i] == -np.sign(V[n]) == -np.sign(EC)
+            S.append(int(n))
+        assert len(set(S)) == len(S)
+        sgn = int(np.sign(EC))
+        got = (abs(EC - sgn * len(S) * ONE), len(S), -int(sum(abs(int(V[n])) for n in S)))
+        assert got == channel_bruteforce(V, EC)
+        want_k = int(tc["channel_k"][m])
+        elig = int((np.sign(V) == sgn).sum()) if sgn else 0
+        assert len(S) == min(want_k, elig)
+        if elig < want_k:
+            seen["short"] += 1                         # Eq. (7) missed by want_k - elig steps
+        else:
+            assert got[0] <= HALF
+        if S:
+            seen["flipped"] += 1
+            thr = min(abs(int(V[n])) for n in S)
+            for n in range(N):
+                if np.sign(V[n]) == sgn and n not in S:
+                    assert abs(int(V[n])) <= thr
+                    if abs(int(V[n])) == thr:
+                        assert n > max(q for q in S if abs(int(V[q])) == thr)
+    assert seen["same"] > 0 and seen["flipped"] > 0
+    if kind == "grid":
+        assert seen["zero"] > 0
+
+
+def test_mode_ec_tie_and_running_out_of_candidates():
+    """Hand cases at scale exactly 1 (one element equals qmax = 7 at 4 bits)."""
+    #            x             p               kernel sum   candidate
+    # kernel 0: (7, .3)      -> (0, -.3)       -.3          -.3  (index 1)
+    # kernel 1: (-.45, .35)  -> (+.45, -.35)   +.1          +.45 (index 0)
+    # kernel 2: (-.4, -.45)  -> (+.4, +.45)    +.85         +.45 (index 1)
+    # kernel 3: (-.2, .3)    -> (+.2, -.3)     -.1          -.3  (index 1)
+    # channel sum +.55 -> one flip towards -; kernels 1 and 2 tie at .45: the lower kernel goes
+    w = np.array([[[7.0, 0.3], [-0.45, 0.35], [-0.4, -0.45], [-0.2, 0.3]]], np.float32)
+    codes, _, tr = oracle.quantize_trace(w.reshape(1, 4, 1, 2), 4, oracle.MODE_EC)
+    assert tr["cand_index"].tolist() == [[1, 0, 1, 1]]
+    assert np.sign(tr["cand_value"]).tolist() == [[-1, 1, 1, -1]]
+    assert int(tr["cand_value"][0, 1]) == int(tr["cand_value"][0, 2])
+    assert int(tr["channel_k"][0]) == 1
+    assert codes.reshape(4, 2).tolist() == [[7, 0], [-1, 0], [0, 0], [0, 0]]
+    # running out: one kernel carries the whole sum +1.8, two flips are wanted, the kernel offers
+    # one candidate, so one element flips and the channel is left at +.8 (Eq. 7 missed)
+    w4 = np.array([[[7.0, 0.0, 0.0, 0.0], [-0.45, -0.45, -0.45, -0.45]]], np.float32)
+    codes4, _, tr4 = oracle.quantize_trace(w4.reshape(1, 2, 1, 4), 4, oracle.MODE_EC)
+    assert int(tr4["channel_k"][0]) == 2
+    assert codes4.reshape(2, 4).tolist() == [[7, 0, 0, 0], [-1, 0, 0, 0]]
+    assert abs(int(tr4["channel_sum"][0]) - ONE) > HALF
+    # the full method on the same channel flips two elements inside the kernel and ends at -.2
+    codes5, _ = oracle.quantize(w4.reshape(1, 2, 1, 4), 4, MODE_EKC)
+    assert codes5.reshape(2, 4).tolist() == [[7, 0, 0, 0], [-1, -1, 0, 0]]
