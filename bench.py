@@ -6,6 +6,12 @@ SQuant-C, int8 emit) over the whole workload, as ONE batched library call, with 
 weights already resident in HBM.  Prints one JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5|c1|c2|c3|c4] [--bits 4]
+
+Every step is bracketed by a pair of events on the stream the library launches on, so the
+kernel time of each single step is known; `steps` and `warmup` are what the command line says.
+The defaults (3 warm-up steps, 20 timed ones) are a cold protocol: the first tens of launches
+after an idle period run while the GPU settles its clocks, which is what a one-shot
+quantization of a network sees.  A long warm-up (--warmup 100) shows the settled rate.
 """
 from __future__ import annotations
 
@@ -74,12 +80,63 @@ def cpu_model() -> str:
     return "unknown"
 
 
+def timed_steps(torch, step, warmup: int, steps: int):
+    """`warmup` untimed steps, then `steps` timed ones: wall time per step (synchronised on both
+    sides) and the elapsed time of every single step between two events recorded on the stream
+    the library launches on (torch's current stream)."""
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for e0, e1 in ev:
+        e0.record()
+        step()
+        e1.record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    return elapsed * 1e3 / max(steps, 1), [e0.elapsed_time(e1) for e0, e1 in ev]
+
+
+def algorithmic_bytes(n_params: int, n_channels: int, wtype: str, output: str) -> float:
+    """Bytes read + written per weight (4 + 1 in the headline configuration), 4 B per scale."""
+    in_bytes = {"f32": 4.0, "f16": 2.0, "bf16": 2.0}[wtype]
+    out_bytes = {"int8": 1.0, "int4": 0.5, "f32": 4.0, "bf16": 2.0}[output]
+    return (in_bytes + out_bytes) * n_params + 4.0 * n_channels
+
+
+def spread(np, kernel_ms):
+    k = np.asarray(kernel_ms, dtype=np.float64)
+    return {"kernel_ms_avg": round(float(k.mean()), 4), "kernel_ms_median": round(float(np.median(k)), 4),
+            "kernel_ms_min": round(float(k.min()), 4), "kernel_ms_p10": round(float(np.percentile(k, 10)), 4),
+            "kernel_ms_p90": round(float(np.percentile(k, 90)), 4), "kernel_ms_max": round(float(k.max()), 4)}
+
+
+def extra_line(torch, np, sq, name, dws, n_params, n_channels, wtype, output, bits, warmup, steps):
+    """One secondary configuration: same protocol, its own algorithmic bytes and fraction."""
+    plan = sq.BatchPlan(dws, sq.OUTPUTS[output])
+    ms_per_step, kernel_ms = timed_steps(torch, lambda: plan.run(bits, sq.MODE_EKC), warmup, steps)
+    algo = algorithmic_bytes(n_params, n_channels, wtype, output)
+    k_avg = float(np.mean(kernel_ms))
+    out = {"name": name, "weight_type": wtype, "output": output, "bits": bits, "mode": "EKC",
+           "weights": n_params, "ms_per_step": round(ms_per_step, 4),
+           "gparams_per_s": round(n_params / (ms_per_step * 1e-3) / 1e9, 2),
+           "algorithmic_bytes_per_launch": algo,
+           "achieved_gbs": round(algo / (k_avg * 1e-3) / 1e9, 1),
+           "frac": round(algo / (k_avg * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    out.update(spread(np, kernel_ms))
+    log(f"[bench] extra {name}: kernel avg {k_avg:.4f} ms, {out['achieved_gbs']:.0f} GB/s "
+        f"({100 * out['frac']:.1f}% of peak)")
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=50,
-                    help="untimed steps first; the GPU needs a few tens of launches to settle its clocks")
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3, help="untimed steps first")
     ap.add_argument("--workload", default="c5", choices=sorted(WORKLOADS))
     ap.add_argument("--bits", type=int, default=4)
     ap.add_argument("--mode", default="EKC", choices=["E", "EK", "EKC", "EC"],
@@ -95,6 +152,8 @@ def main() -> int:
     ap.add_argument("--wtype", default="f32", choices=["f32", "f16", "bf16"],
                     help="element type the weights are handed over in (headline: f32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true",
+                    help="skip the secondary configurations reported under \"extra\"")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for HBM byte counters)")
     args = ap.parse_args()
@@ -154,44 +213,23 @@ def main() -> int:
         torch.cuda.synchronize()
         del a_, b_
 
-    def step():
-        plan.run(args.bits, mode)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-
-    sq.squant_kernel_timer_enable(max(args.steps, 1))
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    kernel_ms = [sq.squant_kernel_timer_elapsed_ms(c) for c in range(args.steps)]
-    sq.squant_kernel_timer_enable(0)
-
-    ms_per_step = elapsed * 1e3 / max(args.steps, 1)
-    value = n_params * args.steps / elapsed / 1e9
+    ms_per_step, kernel_ms = timed_steps(torch, lambda: plan.run(args.bits, mode), args.warmup, args.steps)
+    value = n_params / (ms_per_step * 1e-3) / 1e9
     k_avg_ms = float(np.mean(kernel_ms))
-    # bytes read + written per weight (4 + 1 in the headline configuration), 4 B per scale
-    in_bytes = {"f32": 4.0, "f16": 2.0, "bf16": 2.0}[args.wtype]
-    out_bytes = {"int8": 1.0, "int4": 0.5, "f32": 4.0, "bf16": 2.0}[args.output]
-    algo_bytes = (in_bytes + out_bytes) * n_params + 4.0 * n_channels
+    algo_bytes = algorithmic_bytes(n_params, n_channels, args.wtype, args.output)
     achieved = algo_bytes / (k_avg_ms * 1e-3) / 1e9
     headline_io = args.output == "int8" and args.wtype == "f32"
     traffic = (load_traffic()
                if args.workload == "c5" and args.tensors is None and headline_io else None)
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                "kernel": "squant solver kernel(s) of the batched call",
-                "kernel_ms_avg": round(k_avg_ms, 4), "kernel_ms_median": round(float(np.median(kernel_ms)), 4),
-                "kernel_ms_min": round(float(np.min(kernel_ms)), 4),
+                "kernel": "squant solver kernel(s) of the batched call, event pair around every step",
                 "algorithmic_bytes_per_launch": algo_bytes}
-    if os.environ.get("SQUANT_BENCH_TRACE"):
-        log("[bench] kernel ms per step: " + " ".join(f"{v:.3f}" for v in kernel_ms))
+    roofline.update(spread(np, kernel_ms))
+    roofline["kernel_ms_steps"] = [round(float(v), 4) for v in kernel_ms]
     log(f"[bench] {ms_per_step:.4f} ms/step wall, kernel avg {k_avg_ms:.4f} ms -> "
         f"{value:.1f} Gparams/s, {achieved:.0f} GB/s algorithmic ({100 * achieved / HBM_PEAK_GBS:.1f}% of peak)")
+    log("[bench] kernel ms per step: " + " ".join(f"{v:.3f}" for v in kernel_ms))
 
     # ---- CPU baseline: the reference solver as it stands, on this machine's host cores ----
     cpu_baseline = None
@@ -229,12 +267,33 @@ def main() -> int:
                                    else f"first {len(host_sample)} tensors of the workload") +
                                   f" ({sample_params} weights), {args.mode}, {threads} threads over output channels",
                         "single_thread_value": round(p1 / cpu1_s / 1e9, 5),
+                        "single_thread_sample": f"first {n1} tensors of the sample ({p1} weights), 1 thread",
                         "cpu_model": cpu_model(),
                         "gpu_mismatches_on_sample": mism}
         log(f"[bench] CPU reference: {sample_params / cpu_s / 1e6:.1f} Mparams/s on {threads} threads, "
             f"{p1 / cpu1_s / 1e6:.1f} Mparams/s on 1; GPU mismatches on the sample: {mism}")
         if mism:
             log("[bench] ERROR: GPU output differs from the CPU reference")
+
+    # ---- secondary configurations (same protocol; headline fields above are unaffected) ----
+    extra = []
+    if not args.no_extra and args.workload == "c5" and not args.shape and args.tensors is None \
+            and headline_io and args.mode == "EKC" and args.bits == 4:
+        del plan
+        extra.append(extra_line(torch, np, sq, "c5, float32 weights -> packed 4-bit codes", dws, n_params,
+                                n_channels, "f32", "int4", 4, args.warmup, args.steps))
+        d16 = [w.to(torch.float16) for w in dws]
+        del dws
+        extra.append(extra_line(torch, np, sq, "c5, binary16 weights -> int8 codes", d16, n_params,
+                                n_channels, "f16", "int8", 4, args.warmup, args.steps))
+        del d16
+        torch.cuda.empty_cache()
+        for wl, bits in (("c2", 4), ("c3", 4), ("c3", 8), ("c4", 4)):
+            sp = synth.config_specs(WORKLOADS[wl][0])
+            ws = [torch.from_numpy(synth.generate(s_)).to(dev) for s_ in sp]
+            extra.append(extra_line(torch, np, sq, f"{wl} layer set ({len(sp)} tensors, cache resident), {bits} bit",
+                                    ws, sum(s_.numel for s_ in sp), sum(s_.shape[0] for s_ in sp),
+                                    "f32", "int8", bits, args.warmup, args.steps))
 
     out = {
         "metric": "Gparams/s quantized (4-bit, SQuant-EKC) + achieved HBM GB/s vs peak",
@@ -246,7 +305,7 @@ def main() -> int:
                    "weight_type": args.wtype, "output": args.output,
                    "tensors": len(specs), "weights": n_params, "output_channels": n_channels,
                    "seed": synth.DEFAULT_SEED},
-        "roofline": roofline, "cpu_baseline": cpu_baseline,
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "extra": extra,
     }
     print(json.dumps(out), flush=True)
     return 1 if (cpu_baseline and cpu_baseline["gpu_mismatches_on_sample"]) else 0

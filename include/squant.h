@@ -29,11 +29,11 @@
  * Conventions for every entry point
  *   - pointers named d_* are DEVICE pointers (HIP), h_* are HOST pointers;
  *   - the caller owns every buffer; the library allocates no device memory and keeps
- *     no state between calls (the opt-in kernel timer below excepted);
+ *     no state between calls;
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream); calls
  *     enqueue work and return; outputs are valid once the stream has been synchronised;
  *     the calls only launch kernels (no allocation, no memset, no host synchronisation),
- *     so they may be captured into a HIP graph (with the kernel timer off);
+ *     so they may be captured into a HIP graph;
  *   - codes must not alias the weights; inputs must be finite (NaN/Inf: memory
  *     safe, result unspecified);
  *   - arguments are checked on the host before anything is launched and an
@@ -63,7 +63,7 @@ typedef enum {
   SQUANT_ERR_SHAPE = 2,     /* a dimension is <= 0, or the sizes overflow */
   SQUANT_ERR_BITS = 3,      /* bits outside [2, 8] */
   SQUANT_ERR_MODE = 4,      /* unknown mode */
-  SQUANT_ERR_WORKSPACE = 5, /* workspace missing or too small */
+  SQUANT_ERR_WORKSPACE = 5, /* a workspace size without a workspace pointer */
   SQUANT_ERR_DEVICE = 6,    /* a HIP call failed */
   SQUANT_ERR_UNSUPPORTED = 7, /* one output channel (cin*kh*kw) exceeds what one workgroup's LDS holds */
   SQUANT_ERR_FORMAT = 8     /* unknown weight or output type, or a buffer misaligned for its element type */
@@ -111,17 +111,18 @@ int squant_quantize(const float* d_w, int32_t cout, int32_t cin, int32_t kh, int
                     int32_t bits, squant_mode_t mode, int8_t* d_codes, float* d_scales,
                     void* stream);
 
-/* Device bytes squant_quantize_batched asks for as workspace.  (The present kernels carry
- * the tensor descriptors in their kernel arguments, up to 256 per launch, and do not touch
- * the workspace; it stays part of the contract and is validated.) */
+/* Device bytes squant_quantize_batched asks for as workspace: 0.  The kernels carry the
+ * tensor descriptors in their kernel arguments (up to 256 per launch) and need no memory
+ * beyond the inputs and outputs; the size calls and the workspace arguments stay in the
+ * signatures so that callers written against them keep working. */
 size_t squant_batched_workspace_bytes(int32_t n_tensors);
 
 /* Quantize a set of tensors (the layers of a network are independent, Section 4.2)
  * with a few launches for the whole set instead of one per tensor.
  * h_tensors: HOST array of n_tensors descriptors holding DEVICE pointers; it may be
- * freed or reused as soon as the call returns.  d_workspace: caller-allocated device
- * memory of at least squant_batched_workspace_bytes(n_tensors), 16-byte aligned; it must
- * stay untouched until the stream has passed this call.  n_tensors = 0 is a no-op. */
+ * freed or reused as soon as the call returns.  d_workspace / workspace_bytes: may be
+ * NULL / 0 (squant_batched_workspace_bytes is 0); a buffer that is passed is neither read
+ * nor written; a size without a pointer is SQUANT_ERR_WORKSPACE.  n_tensors = 0 is a no-op. */
 int squant_quantize_batched(const squant_tensor_t* h_tensors, int32_t n_tensors, int32_t bits,
                             squant_mode_t mode, void* d_workspace, size_t workspace_bytes,
                             void* stream);
@@ -164,13 +165,13 @@ typedef struct {
   int32_t zero_point;
 } squant_act_range_t;
 
-/* Device bytes squant_activation_ranges asks for as workspace (validated, not touched at
- * present: the layer descriptors travel in the kernel arguments, 256 per launch). */
+/* Device bytes squant_activation_ranges asks for as workspace: 0 (the layer descriptors
+ * travel in the kernel arguments, 256 per launch). */
 size_t squant_activation_workspace_bytes(int32_t n_layers);
 
 /* h_layers: HOST array of n_layers descriptors holding DEVICE pointers (reusable as soon as
  * the call returns); d_ranges: device, n_layers results; d_workspace as for
- * squant_quantize_batched (at least squant_activation_workspace_bytes, 16-byte aligned).
+ * squant_quantize_batched (may be NULL / 0).
  * bits in [2, 16], n_sigma finite and >= 0 (SQUANT_ERR_BITS / SQUANT_ERR_SHAPE otherwise). */
 int squant_activation_ranges(const squant_bn_t* h_layers, int32_t n_layers, float n_sigma,
                              int32_t bits, squant_act_range_t* d_ranges, void* d_workspace,
@@ -183,7 +184,7 @@ typedef struct {
   squant_bn_t bn;
 } squant_layer_t;
 
-/* Device bytes squant_quantize_network needs. */
+/* Device bytes squant_quantize_network asks for as workspace: 0. */
 size_t squant_network_workspace_bytes(int32_t n_layers);
 
 /* The data-free pipeline of Section 4 for a whole network in one call: every weight tensor
@@ -199,18 +200,6 @@ int squant_quantize_network(const squant_layer_t* h_layers, int32_t n_layers, in
  * is for 16-byte aligned weights with cin a multiple of 4; for 1x1 and 3x3 kernels other
  * tensors go through the generic kernel, which holds more per element and takes less. */
 int64_t squant_max_channel_elems(int32_t kh, int32_t kw);
-
-/* Measurement aid (opt-in, per calling thread; the only state the library keeps).
- * squant_kernel_timer_enable(slots) creates `slots` pairs of HIP events (0 releases them
- * and switches the timer off).  While it is on, every squant_quantize /
- * squant_quantize_batched call of this thread records one event on its stream before its
- * first solver kernel and one after its last; call number c since the enable uses pair c mod slots.
- * squant_kernel_timer_elapsed_ms(c, h_ms) waits for call c's second event and writes its
- * elapsed milliseconds to the HOST float *h_ms; SQUANT_ERR_SHAPE if call c was never
- * timed or its pair has been reused. */
-int squant_kernel_timer_enable(int32_t slots);
-int64_t squant_kernel_timer_calls(void);
-int squant_kernel_timer_elapsed_ms(int64_t call, float* h_ms);
 
 const char* squant_status_string(int status);
 int squant_version(void);

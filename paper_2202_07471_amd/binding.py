@@ -91,11 +91,6 @@ def lib():
         L.squant_status_string.argtypes = [ctypes.c_int]
         L.squant_status_string.restype = ctypes.c_char_p
         L.squant_version.restype = ctypes.c_int
-        L.squant_kernel_timer_enable.argtypes = [i32]
-        L.squant_kernel_timer_enable.restype = ctypes.c_int
-        L.squant_kernel_timer_calls.restype = ctypes.c_int64
-        L.squant_kernel_timer_elapsed_ms.argtypes = [ctypes.c_int64, ctypes.POINTER(ctypes.c_float)]
-        L.squant_kernel_timer_elapsed_ms.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -120,20 +115,6 @@ def squant_batched_workspace_bytes(n_tensors: int) -> int:
     return int(lib().squant_batched_workspace_bytes(n_tensors))
 
 
-def squant_kernel_timer_enable(slots: int) -> None:
-    _check(lib().squant_kernel_timer_enable(slots))
-
-
-def squant_kernel_timer_calls() -> int:
-    return int(lib().squant_kernel_timer_calls())
-
-
-def squant_kernel_timer_elapsed_ms(call: int) -> float:
-    ms = ctypes.c_float(0.0)
-    _check(lib().squant_kernel_timer_elapsed_ms(call, ctypes.byref(ms)))
-    return float(ms.value)
-
-
 def _check(rc: int):
     if rc != 0:
         raise SQuantError(rc, squant_status_string(rc))
@@ -150,6 +131,10 @@ def _shape4(w: torch.Tensor) -> Tuple[int, int, int, int]:
 def _stream_ptr(stream) -> int:
     s = stream if stream is not None else torch.cuda.current_stream()
     return int(s.cuda_stream)
+
+
+def _ws_ptr(ws):
+    return ws.data_ptr() if ws is not None else None
 
 
 def _check_weight(w: torch.Tensor):
@@ -233,12 +218,13 @@ class BatchPlan:
             self.scales.append(s)
             self.desc[i] = squant_tensor_t(w.data_ptr(), c.data_ptr(), s.data_ptr(), cout, cin, kh, kw)
         self.n = n
-        self.ws_bytes = squant_batched_workspace_bytes(n)
-        self.workspace = torch.empty(max(self.ws_bytes, 16), dtype=torch.uint8, device=dev)
+        self.ws_bytes = squant_batched_workspace_bytes(n)      # 0: the library needs none
+        self.workspace = (torch.empty(self.ws_bytes, dtype=torch.uint8, device=dev)
+                          if self.ws_bytes else None)
 
     def run(self, bits: int, mode: int = MODE_EKC, stream=None):
         _check(lib().squant_quantize_batched_ex(self.desc, self.n, self.wtype, bits, mode,
-                                                self.output, self.workspace.data_ptr(),
+                                                self.output, _ws_ptr(self.workspace),
                                                 self.ws_bytes, _stream_ptr(stream)))
         return self.codes, self.scales
 
@@ -250,7 +236,7 @@ def squant_quantize_batched(weights: Iterable[torch.Tensor], bits: int, mode: in
     for w in ws:
         _check_weight(w)
     plan = BatchPlan(ws)
-    _check(lib().squant_quantize_batched(plan.desc, plan.n, bits, mode, plan.workspace.data_ptr(),
+    _check(lib().squant_quantize_batched(plan.desc, plan.n, bits, mode, _ws_ptr(plan.workspace),
                                          plan.ws_bytes, _stream_ptr(stream)))
     return plan.codes, plan.scales
 
@@ -285,8 +271,8 @@ def squant_activation_ranges(bn_layers, n_sigma: float, bits: int, stream=None):
     dev = layers[0][0].device if n else torch.device("cuda")
     out = torch.zeros(max(n, 1) * 4, dtype=torch.float32, device=dev)
     ws_bytes = int(lib().squant_activation_workspace_bytes(n))
-    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
-    _check(lib().squant_activation_ranges(desc, n, n_sigma, bits, out.data_ptr(), ws.data_ptr(),
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev) if ws_bytes else None
+    _check(lib().squant_activation_ranges(desc, n, n_sigma, bits, out.data_ptr(), _ws_ptr(ws),
                                           ws_bytes, _stream_ptr(stream)))
     torch.cuda.synchronize()
     return _ranges_from(out, n)
@@ -318,9 +304,9 @@ def squant_quantize_network(layers, weight_bits: int, mode: int = MODE_EKC, act_
             desc[i] = squant_layer_t(wt, squant_bn_t(g.data_ptr(), b.data_ptr(), g.numel(), int(bool(relu))))
     out = torch.zeros(max(n, 1) * 4, dtype=torch.float32, device=dev)
     ws_bytes = int(lib().squant_network_workspace_bytes(n))
-    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=dev)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev) if ws_bytes else None
     _check(lib().squant_quantize_network(desc, n, weight_bits, mode, act_bits, n_sigma, out.data_ptr(),
-                                         ws.data_ptr(), ws_bytes, _stream_ptr(stream)))
+                                         _ws_ptr(ws), ws_bytes, _stream_ptr(stream)))
     torch.cuda.synchronize()
     ranges = _ranges_from(out, n)
     return codes, scales, [r if layers[i][1] is not None else None for i, r in enumerate(ranges)]

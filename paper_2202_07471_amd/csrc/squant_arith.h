@@ -31,11 +31,8 @@ SQ_HD int32_t imax2(int32_t a, int32_t b) { return a > b ? a : b; }
 SQ_HD int32_t imin2(int32_t a, int32_t b) { return a < b ? a : b; }
 SQ_HD int32_t imax3(int32_t a, int32_t b, int32_t c) { return imax2(imax2(a, b), c); }
 SQ_HD int32_t imin3(int32_t a, int32_t b, int32_t c) { return imin2(imin2(a, b), c); }
-#ifndef SQ_OPT_MED3_ASM
-#define SQ_OPT_MED3_ASM 1
-#endif
 SQ_HD int32_t imed3(int32_t a, int32_t b, int32_t c) {
-#if defined(__HIP_DEVICE_COMPILE__) && SQ_OPT_MED3_ASM
+#if defined(__HIP_DEVICE_COMPILE__)  // the compiler does not form the instruction from min / max
   int32_t r;
   asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
   return r;
@@ -76,6 +73,54 @@ SQ_HD void top5_of_9(const int32_t (&x)[9], int32_t (&t)[5]) {
   t[2] = imax2(D, C);
   t[3] = imax2(t1, E);
   t[4] = imax2(t2, G);
+}
+
+// The same network on unsigned keys.
+SQ_HD uint32_t umax2(uint32_t a, uint32_t b) { return a > b ? a : b; }
+SQ_HD uint32_t umin2(uint32_t a, uint32_t b) { return a < b ? a : b; }
+SQ_HD uint32_t umax3(uint32_t a, uint32_t b, uint32_t c) { return umax2(umax2(a, b), c); }
+SQ_HD uint32_t umin3(uint32_t a, uint32_t b, uint32_t c) { return umin2(umin2(a, b), c); }
+SQ_HD uint32_t umed3(uint32_t a, uint32_t b, uint32_t c) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  uint32_t r;
+  asm("v_med3_u32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+#else
+  return umax2(umin2(a, b), umin2(umax2(a, b), c));
+#endif
+}
+SQ_HD void top5_of_9u(const uint32_t (&x)[9], uint32_t (&t)[5]) {
+  uint32_t hi[3], mid[3], lo[3];
+#pragma unroll
+  for (int j = 0; j < 3; ++j) {
+    hi[j] = umax3(x[j], x[j + 3], x[j + 6]);
+    mid[j] = umed3(x[j], x[j + 3], x[j + 6]);
+    lo[j] = umin3(x[j], x[j + 3], x[j + 6]);
+  }
+  const uint32_t a = umax3(hi[0], hi[1], hi[2]);
+  const uint32_t b = umed3(hi[0], hi[1], hi[2]);
+  const uint32_t c = umin3(hi[0], hi[1], hi[2]);
+  const uint32_t d = umax3(mid[0], mid[1], mid[2]);
+  const uint32_t e = umed3(mid[0], mid[1], mid[2]);
+  const uint32_t g = umax3(lo[0], lo[1], lo[2]);
+  const uint32_t B = umax2(b, d), D = umin2(b, d);
+  const uint32_t C = umax3(c, e, g), E = umed3(c, e, g), G = umin3(c, e, g);
+  const uint32_t t1 = umin2(D, C), t2 = umin2(t1, E);
+  t[0] = a;
+  t[1] = B;
+  t[2] = umax2(D, C);
+  t[3] = umax2(t1, E);
+  t[4] = umax2(t2, G);
+}
+
+// Bits 0..8 of f (one per element of a 3x3 kernel) as 0/1 bytes in the layout of the
+// kernel's packed codes: b0 = elements 0-3, b1 = elements 4-7, b2 = element 8.  A 4-bit
+// field times 0x204081 puts bit i at positions i, i + 7, i + 14, i + 21, of which
+// 0, 8, 16, 24 are kept: bit i in byte i.
+SQ_HD void spread_flip_bits(uint32_t f, uint32_t& b0, uint32_t& b1, uint32_t& b2) {
+  b0 = ((f & 15u) * 0x204081u) & 0x01010101u;
+  b1 = (((f >> 4) & 15u) * 0x204081u) & 0x01010101u;
+  b2 = (f >> 8) & 1u;
 }
 
 }  // namespace squant

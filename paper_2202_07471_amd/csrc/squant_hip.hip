@@ -87,14 +87,6 @@ int check_shape(int32_t cout, int32_t cin, int32_t kh, int32_t kw) {
   return SQUANT_OK;
 }
 
-// Opt-in measurement aid: a ring of event pairs around the solver kernels of each call.
-struct KernelTimer {
-  std::vector<hipEvent_t> start, stop;
-  int64_t calls = 0;  // calls timed since enable
-};
-thread_local KernelTimer g_timer;
-void timer_mark(bool start, hipStream_t st);
-
 constexpr int kMixed = 100;      // Group::variant of a launch of squant_channel_mixed
 constexpr int kMixedWave = 101;  // the same for the tensors whose channels take one wave each
 constexpr int kKsMixed = 102;    // Group::variant of a launch of squant_channel_ks_mixed
@@ -300,21 +292,6 @@ int launch_group(const Group& g, int qmax, int mode, int output, int wtype, hipS
   return SQUANT_OK;
 }
 
-void timer_mark(bool start, hipStream_t st) {
-  const size_t slots = g_timer.start.size();
-  if (slots == 0) return;
-  const size_t i = (size_t)(g_timer.calls % (int64_t)slots);
-  if (hipEventRecord(start ? g_timer.start[i] : g_timer.stop[i], st) != hipSuccess)
-    (void)hipGetLastError();
-  if (!start) ++g_timer.calls;
-}
-
-void timer_release() {
-  for (hipEvent_t e : g_timer.start) (void)hipEventDestroy(e);
-  for (hipEvent_t e : g_timer.stop) (void)hipEventDestroy(e);
-  g_timer = KernelTimer{};
-}
-
 }  // namespace
 
 extern "C" {
@@ -333,11 +310,8 @@ int squant_quantize_ex(const void* d_w, squant_wtype_t wtype, int32_t cout, int3
   if (p.lds == 0) return SQUANT_ERR_UNSUPPORTED;
   Group g{p.variant, p.threads, p.lds, {}};
   g.t.push_back(TensorDesc{d_w, d_out, d_scales, cout, cin, (int32_t)K, 0});
-  timer_mark(true, (hipStream_t)stream);
-  const int rc = launch_group(g, (1 << (bits - 1)) - 1, (int)mode, (int)output, (int)wtype,
-                              (hipStream_t)stream);
-  timer_mark(false, (hipStream_t)stream);
-  return rc;
+  return launch_group(g, (1 << (bits - 1)) - 1, (int)mode, (int)output, (int)wtype,
+                      (hipStream_t)stream);
 }
 
 int squant_quantize(const float* d_w, int32_t cout, int32_t cin, int32_t kh, int32_t kw,
@@ -359,10 +333,9 @@ size_t squant_output_bytes(int32_t cout, int32_t cin, int32_t kh, int32_t kw, sq
   return 0;
 }
 
-size_t squant_batched_workspace_bytes(int32_t n_tensors) {
-  if (n_tensors <= 0) return 0;
-  return (size_t)n_tensors * sizeof(TensorDesc);
-}
+// The descriptors travel in the kernel arguments and no kernel needs memory beyond its inputs
+// and outputs, so no call asks for a workspace.
+size_t squant_batched_workspace_bytes(int32_t) { return 0; }
 
 int squant_quantize_batched(const squant_tensor_t* h_tensors, int32_t n_tensors, int32_t bits,
                             squant_mode_t mode, void* d_workspace, size_t workspace_bytes,
@@ -385,9 +358,7 @@ int squant_quantize_batched_ex(const squant_tensor_t* h_tensors, int32_t n_tenso
     if (int rc = check_shape(t.cout, t.cin, t.kh, t.kw)) return rc;
     if (int rc = check_format((int)wtype, (int)output, bits, t.w, t.codes)) return rc;
   }
-  if (!d_workspace || workspace_bytes < squant_batched_workspace_bytes(n_tensors) ||
-      (reinterpret_cast<uintptr_t>(d_workspace) & 15u) != 0)
-    return SQUANT_ERR_WORKSPACE;
+  if (!d_workspace && workspace_bytes != 0) return SQUANT_ERR_WORKSPACE;
   const DeviceLimits lim = device_limits();
   if (!lim.ok) { (void)hipGetLastError(); return SQUANT_ERR_DEVICE; }
 
@@ -468,17 +439,12 @@ int squant_quantize_batched_ex(const squant_tensor_t* h_tensors, int32_t n_tenso
   }
   hipStream_t st = (hipStream_t)stream;
   const int qmax = (1 << (bits - 1)) - 1;
-  timer_mark(true, st);
   for (const auto& g : groups)
     if (int rc = launch_group(g, qmax, (int)mode, (int)output, (int)wtype, st)) return rc;
-  timer_mark(false, st);
   return SQUANT_OK;
 }
 
-size_t squant_activation_workspace_bytes(int32_t n_layers) {
-  if (n_layers <= 0) return 0;
-  return (size_t)n_layers * sizeof(BnDesc);
-}
+size_t squant_activation_workspace_bytes(int32_t) { return 0; }
 
 namespace {
 // Shared by squant_activation_ranges and squant_quantize_network; every descriptor names the
@@ -520,17 +486,11 @@ int squant_activation_ranges(const squant_bn_t* h_layers, int32_t n_layers, floa
     if (l.channels <= 0) return SQUANT_ERR_SHAPE;
     layers.push_back(BnDesc{l.gamma, l.beta, l.channels, l.relu, i, 0});
   }
-  if (!d_workspace || workspace_bytes < squant_activation_workspace_bytes(n_layers) ||
-      (reinterpret_cast<uintptr_t>(d_workspace) & 15u) != 0)
-    return SQUANT_ERR_WORKSPACE;
+  if (!d_workspace && workspace_bytes != 0) return SQUANT_ERR_WORKSPACE;
   return launch_activation_ranges(layers, n_sigma, bits, d_ranges, (hipStream_t)stream);
 }
 
-size_t squant_network_workspace_bytes(int32_t n_layers) {
-  if (n_layers <= 0) return 0;
-  const size_t w = (squant_batched_workspace_bytes(n_layers) + 15) / 16 * 16;
-  return w + squant_activation_workspace_bytes(n_layers);
-}
+size_t squant_network_workspace_bytes(int32_t) { return 0; }
 
 int squant_quantize_network(const squant_layer_t* h_layers, int32_t n_layers, int32_t weight_bits,
                             squant_mode_t mode, int32_t act_bits, float n_sigma,
@@ -550,12 +510,8 @@ int squant_quantize_network(const squant_layer_t* h_layers, int32_t n_layers, in
     if (l.channels <= 0) return SQUANT_ERR_SHAPE;
     bns.push_back(BnDesc{l.gamma, l.beta, l.channels, l.relu, i, 0});
   }
-  if (!d_workspace || workspace_bytes < squant_network_workspace_bytes(n_layers) ||
-      (reinterpret_cast<uintptr_t>(d_workspace) & 15u) != 0)
-    return SQUANT_ERR_WORKSPACE;
-  const size_t w_bytes = (squant_batched_workspace_bytes(n_layers) + 15) / 16 * 16;
-  if (int rc = squant_quantize_batched(weights.data(), n_layers, weight_bits, mode, d_workspace, w_bytes,
-                                       stream))
+  if (!d_workspace && workspace_bytes != 0) return SQUANT_ERR_WORKSPACE;
+  if (int rc = squant_quantize_batched(weights.data(), n_layers, weight_bits, mode, nullptr, 0, stream))
     return rc;
   if (bns.empty()) return SQUANT_OK;
   return launch_activation_ranges(bns, n_sigma, act_bits, d_ranges, (hipStream_t)stream);
@@ -577,39 +533,6 @@ int64_t squant_max_channel_elems(int32_t kh, int32_t kw) {
   return n * K;
 }
 
-int squant_kernel_timer_enable(int32_t slots) {
-  timer_release();
-  if (slots < 0 || slots > 65536) return SQUANT_ERR_SHAPE;
-  for (int32_t i = 0; i < slots; ++i) {
-    hipEvent_t a = nullptr, b = nullptr;
-    if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
-      (void)hipGetLastError();
-      if (a) (void)hipEventDestroy(a);
-      timer_release();
-      return SQUANT_ERR_DEVICE;
-    }
-    g_timer.start.push_back(a);
-    g_timer.stop.push_back(b);
-  }
-  return SQUANT_OK;
-}
-
-int64_t squant_kernel_timer_calls(void) { return g_timer.calls; }
-
-int squant_kernel_timer_elapsed_ms(int64_t call, float* h_ms) {
-  if (!h_ms) return SQUANT_ERR_NULL;
-  const int64_t slots = (int64_t)g_timer.start.size();
-  if (slots == 0 || call < 0 || call >= g_timer.calls || call < g_timer.calls - slots)
-    return SQUANT_ERR_SHAPE;
-  const size_t i = (size_t)(call % slots);
-  if (hipEventSynchronize(g_timer.stop[i]) != hipSuccess ||
-      hipEventElapsedTime(h_ms, g_timer.start[i], g_timer.stop[i]) != hipSuccess) {
-    (void)hipGetLastError();
-    return SQUANT_ERR_DEVICE;
-  }
-  return SQUANT_OK;
-}
-
 const char* squant_status_string(int status) {
   switch (status) {
     case SQUANT_OK: return "ok";
@@ -617,7 +540,7 @@ const char* squant_status_string(int status) {
     case SQUANT_ERR_SHAPE: return "bad shape";
     case SQUANT_ERR_BITS: return "bits must be in [2, 8]";
     case SQUANT_ERR_MODE: return "unknown mode";
-    case SQUANT_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case SQUANT_ERR_WORKSPACE: return "workspace size given without a workspace";
     case SQUANT_ERR_DEVICE: return "HIP call failed";
     case SQUANT_ERR_UNSUPPORTED: return "output channel too large for one workgroup's LDS";
     case SQUANT_ERR_FORMAT: return "unknown weight or output type, or misaligned buffer";
@@ -625,6 +548,6 @@ const char* squant_status_string(int status) {
   }
 }
 
-int squant_version(void) { return 133; }
+int squant_version(void) { return 200; }
 
 }  // extern "C"

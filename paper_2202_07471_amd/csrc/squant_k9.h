@@ -1,15 +1,25 @@
 // SQuant kernel for 3x3 convolutions (K = kh*kw = 9), the bulk of a CNN's weights.
 //
-// One workgroup per output channel, one thread per FOUR 3x3 kernels.  Nothing is staged:
-// thread t reads kernels t, t+G, t+2G, t+3G (G = cin/4) straight from HBM as three 12-byte
+// One workgroup per output channel, one thread per KPT 3x3 kernels.  Nothing is staged:
+// thread t reads kernels t, t+G, t+2G, ... (G = cin/KPT) straight from HBM as three 12-byte
 // vectors each, so neighbouring lanes read neighbouring kernels and the three loads of a
-// wave cover one contiguous 2304-byte span.  From there SQuant-E, SQuant-K and the
-// Algorithm 3 candidate are pure register arithmetic: the k <= 4 largest same-sign
-// perturbations of a kernel come out of a 25-operation three-input (max3/med3/min3) selection network on unique integer
-// keys (|p| in Q23 above a 4-bit "15 - index" tie-break).  LDS only holds the channel's
-// int8 codes, for the channel-wise flips of SQuant-C (run once per channel on the 4
-// candidates each thread holds) and for a coalesced 16-byte write-out; occupancy is left
-// to the register file.
+// wave cover one contiguous 2304-byte span.  Everything up to the channel-wise decision is
+// register arithmetic, written to keep the vector instruction count down (the kernel is
+// bound by instruction issue as much as by memory):
+//   * SQuant-E rounds by adding 1.5 * 2^23 + 128, which leaves code + 128 in the low byte of
+//     the sum's bit pattern, so the nine codes of a kernel are packed into three dwords by
+//     byte permutes, with no conversion;
+//   * the Q23 perturbations stay biased by the bit pattern of 1.5 * 2^23: their sum is
+//     corrected once, and the ranking keys are made from the biased words directly;
+//   * the k <= 4 largest same-sign perturbations come out of a 25-operation three-input
+//     (max3 / med3 / min3) selection network on unique keys (|p| above a 5-bit tie-break that
+//     is also the shift count which turns a key into its element's flip bit);
+//   * SQuant-K leaves a 9-bit flip mask per kernel; SQuant-C toggles one bit of it (flipping
+//     an over-SQuant candidate back clears its bit, flipping an under-SQuant candidate sets
+//     one), and the mask is applied to the packed codes once, after the channel-wise decision.
+// LDS holds the two-sign histogram of SQuant-C (squant_select.h), a ranking list for the
+// histogram bin the selection ends in, and finally the channel's codes for a coalesced
+// 16-byte write-out; occupancy is left to the register file.
 #pragma once
 
 #include "squant_common.h"
@@ -24,93 +34,134 @@ struct alignas(16) K9Shared {
   SelectShared sel;
 };
 
-// SQuant-E, SQuant-K and the candidate update for one 3x3 kernel held in registers.
-// Straight-line code on purpose: the four kernels of a thread are scheduled as one region,
-// and a branch between them was measured to cost 20%.
-//   w, q    the kernel's nine weights are w[9q .. 9q+8]
-//   FAST    take the quotients through the reciprocal rs = 1/s
-//   MODE    SQUANT_MODE_*
-//   cf      out: the final codes as floats, biased by +128
-//   esum    += the kernel's Q23 perturbation sum after SQuant-K
-//   cand_w  the kernel's SQuant-C candidate as a candidate word (squant_select.h)
-//   cand_i  its element index 0..8
-//   zero    |= 1 << Q when the kernel's perturbation sum is exactly 0 (its candidate is then
-//           worked out separately, see k9_zero_sum_candidate)
-template <int NW, bool FAST, int MODE>
-__device__ __forceinline__ void k9_solve(const float (&w)[NW], int q, float s, float rs, float qmaxf,
-                                         float (&cf)[9], int32_t& esum, uint32_t& cand_w,
-                                         int& cand_i, uint32_t& zero) {
-  const int W0 = 9 * q;  // a constant once the caller's loop over q is unrolled
-  float c[9];
-  int32_t P[9];
+// Adding kRoundMagic to a clamped quotient |x| <= 127 rounds it to an integer, half to even
+// (the sum lies in [2^23, 2^24), where binary32 has unit spacing, and the constant is even),
+// and the sum's bit pattern ends in the byte code + 128.
+constexpr float kRoundMagic = 12583040.0f;      // 1.5 * 2^23 + 128
+constexpr float kQ23Magic = 12582912.0f;        // 1.5 * 2^23
+constexpr uint32_t kQ23Bias = 0x4B400000u;      // its bit pattern: biased perturbation = kQ23Bias + P
+
+// What a thread keeps of one 3x3 kernel between SQuant-K and the write-out.
+struct K9Kernel {
+  uint32_t d0, d1, d2;  // codes + 128: elements 0-3, 4-7, 8 (the upper bytes of d2 are not codes)
+  uint32_t flips;       // bit i: element i moves one step against the sign of the kernel's sum
+  uint32_t sm;          // 0 when that sign is +, ~0 when it is -
+  uint32_t cand;        // the SQuant-C candidate as a candidate word (squant_select.h)
+  uint32_t cand_bit;    // 1 << its element index
+};
+
+// The low bytes of four words as one dword.
+__device__ __forceinline__ uint32_t pack_low_bytes(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+  return __builtin_amdgcn_perm(b, a, 0x0c0c0400u) | __builtin_amdgcn_perm(d, c, 0x04000c0cu);
+}
+
+// SQuant-E on the nine weights w[0..8] of one kernel (Algorithm 1, rounding and element
+// perturbation): packed biased codes and the nine biased Q23 perturbations.
+//   FAST  take the quotients through the reciprocal rs = 1/s
+template <bool FAST>
+__device__ __forceinline__ void k9_round(const float* w, float s, float rs, float qmaxf, K9Kernel& kk,
+                                         uint32_t (&pb)[9]) {
+  uint32_t tb[9];
 #pragma unroll
   for (int i = 0; i < 9; ++i) {
     // x = w / s: either way the IEEE binary32 quotient
-    const float x = FAST ? div_by_reciprocal(w[W0 + i], s, rs) : w[W0 + i] / s;
+    const float x = FAST ? div_by_reciprocal(w[i], s, rs) : w[i] / s;
     const float xc = __builtin_amdgcn_fmed3f(x, -qmaxf, qmaxf);
-    c[i] = rintf(xc);
-    const float p = c[i] - xc;  // exact
-    // Q23: p * 2^23 + 1.5 * 2^23 lies in [2^23, 2^24], where a float is an integer, so the one
-    // rounding of the FMA is the round-half-even of p * 2^23 and the integer sits in the
-    // low mantissa bits
-    P[i] = __float_as_int(__builtin_fmaf(p, 8388608.0f, 12582912.0f)) - 0x4B400000;
+    const float t = xc + kRoundMagic;
+    const float c = t - kRoundMagic;  // round-half-even(xc), exact
+    const float p = c - xc;           // exact
+    // Q23: p * 2^23 + 1.5 * 2^23 lies in [2^23, 2^24], so the one rounding of the FMA is the
+    // round-half-even of p * 2^23 and the integer sits in the low mantissa bits
+    pb[i] = __float_as_uint(__builtin_fmaf(p, 8388608.0f, kQ23Magic));
+    tb[i] = __float_as_uint(t);
   }
-  cand_w = kNoCandidate;
-  cand_i = 0;
-  if (MODE == SQUANT_MODE_E) {
+  kk.d0 = pack_low_bytes(tb[0], tb[1], tb[2], tb[3]);
+  kk.d1 = pack_low_bytes(tb[4], tb[5], tb[6], tb[7]);
+  kk.d2 = tb[8];
+}
+
+// SQuant-K and the perturbation update for one kernel (Algorithm 2 on the kernel,
+// Algorithm 3): the flip mask, the sign, the candidate; esum += the kernel's Q23
+// perturbation sum after SQuant-K; returns |sum before SQuant-K| (0: the candidate of such
+// a kernel is worked out separately, see k9_recheck_kernel).
+template <int MODE>
+__device__ __forceinline__ uint32_t k9_flip(const uint32_t (&pb)[9], K9Kernel& kk, int32_t& esum) {
+  constexpr bool kCand = MODE == SQUANT_MODE_EKC || MODE == SQUANT_MODE_EC;
+  uint32_t eb = 0;
 #pragma unroll
-    for (int i = 0; i < 9; ++i) cf[i] = c[i] + 128.0f;
-    return;
+  for (int i = 0; i < 9; ++i) eb += pb[i];
+  const int32_t E = (int32_t)(eb - 9u * kQ23Bias);
+  const uint32_t sm = (uint32_t)(E >> 31);  // all ones when the sum is negative
+  const uint32_t A = ((uint32_t)E ^ sm) - sm;  // |E|
+  kk.sm = sm;
+
+  // unique keys, larger = flips earlier.  For a positive sum (pb << 5) = base + 32 P, for a
+  // negative one (~pb << 5) = base' - 32 P; the low five bits hold 31 - i.  Elements with the
+  // sign of the sum are exactly those with key >= base + 32.
+  uint32_t key[9];
+#pragma unroll
+  for (int i = 0; i < 9; ++i) key[i] = ((pb[i] ^ sm) << 5) | (uint32_t)(31 - i);
+  const uint32_t base = sm ? ((~kQ23Bias) << 5) : (kQ23Bias << 5);
+
+  if (MODE == SQUANT_MODE_EC) {
+    // no kernel-wise flip: k = 0, the candidate is the largest same-sign perturbation
+    esum += E;
+    kk.flips = 0;
+    const uint32_t ck = umax3(umax3(key[0], key[1], key[2]), umax3(key[3], key[4], key[5]),
+                              umax3(key[6], key[7], key[8]));
+    const int32_t rel = (int32_t)(ck - base);
+    kk.cand = rel >= 32 ? (((uint32_t)rel >> 5) | (sm & (1u << 23))) : kNoCandidate;
+    kk.cand_bit = 0x80000000u >> (ck & 31u);
+    return A;
   }
 
-  // ---- SQuant-K (Algorithm 2 on one kernel) ----
-  int32_t E = 0;
-#pragma unroll
-  for (int i = 0; i < 9; ++i) E += P[i];
-  const int32_t smask = E >> 31;                 // all ones when the sum is negative
-  const int32_t A = (E ^ smask) - smask;         // |E|
-  const int32_t k = (MODE == SQUANT_MODE_EC) ? 0 : (int32_t)((uint32_t)(A + kHalf - 1) >> 23);
-  const int32_t r = A - (k << 23);               // |sum| left after k flips, < 0: over SQuant
-  esum += (r ^ smask) - smask;
-  zero |= (E == 0 ? 1u : 0u) << q;
+  const uint32_t tt = A + (uint32_t)(kHalf - 1);  // k = tt >> 23 (an exact half rounds down)
+  const int32_t r = (int32_t)(tt & 0x7FFFFFu) - (kHalf - 1);  // |sum| left after k flips, < 0: over SQuant
+  esum += (int32_t)(((uint32_t)r ^ sm) - sm);
 
-  // unique keys: 16 |p| + (15 - i) >= 16 for the elements with the sign of the sum, < 16 for
-  // all others; |P| <= 2^22 fits the 24-bit multiply-add
-  int32_t key[9], srt[5];
-#pragma unroll
-  for (int i = 0; i < 9; ++i) key[i] = __mul24(P[i], smask ? -16 : 16) + (15 - i);
-  top5_of_9(key, srt);
-  int32_t s_km1 = 0x7fffffff, s_k = srt[0];      // (k-th, (k+1)-th) largest key, 1-based
-  if (k >= 1) { s_km1 = srt[0]; s_k = srt[1]; }
-  if (k >= 2) { s_km1 = srt[1]; s_k = srt[2]; }
-  if (k >= 3) { s_km1 = srt[2]; s_k = srt[3]; }
-  if (k >= 4) { s_km1 = srt[3]; s_k = srt[4]; }
-
-  // flip the k largest: code -= sign(E)
-  const float flip = smask ? 129.0f : 127.0f;
-#pragma unroll
-  for (int i = 0; i < 9; ++i) cf[i] = c[i] + (key[i] >= s_km1 ? flip : 128.0f);
-  if (MODE == SQUANT_MODE_EK) return;
+  uint32_t srt[5];
+  top5_of_9u(key, srt);
+  const bool k1 = tt >= (1u << 23), k2 = tt >= (2u << 23), k3 = tt >= (3u << 23), k4 = tt >= (4u << 23);
+  // a key's low five bits are 31 - i, so 2^31 >> key is bit i (shift counts are taken mod 32)
+  const uint32_t m0 = 0x80000000u >> (srt[0] & 31u);
+  const uint32_t m1 = m0 | (0x80000000u >> (srt[1] & 31u));
+  const uint32_t m2 = m1 | (0x80000000u >> (srt[2] & 31u));
+  const uint32_t m3 = m2 | (0x80000000u >> (srt[3] & 31u));
+  kk.flips = k4 ? m3 : k3 ? m2 : k2 ? m1 : k1 ? m0 : 0u;
+  if (!kCand) return A;
 
   // ---- perturbation update (Algorithm 3): the kernel's candidate for SQuant-C ----
   const bool over = r < 0;
-  const int32_t ck = over ? s_km1 : s_k;         // over: last flipped; under: first un-flipped
-  const uint32_t mag = (uint32_t)ck >> 4;        // |p| of that element before any flip
+  const uint32_t nxt = k4 ? srt[4] : k3 ? srt[3] : k2 ? srt[2] : k1 ? srt[1] : srt[0];  // (k+1)-th
+  const uint32_t thr = k4 ? srt[3] : k3 ? srt[2] : k2 ? srt[1] : srt[0];                // k-th, k >= 1
+  const uint32_t ck = over ? thr : nxt;  // over: last flipped; under: first un-flipped
+  const int32_t rel = (int32_t)(ck - base);         // 32 |p| + (31 - i) for a same-sign element
+  const uint32_t mag = (uint32_t)rel >> 5;          // |p| of that element before any flip
   // over: the post-flip value kOne - mag with the sign opposite to the sum; under: mag with
   // the sign of the sum
-  const uint32_t absv = over ? (uint32_t)kOne - mag : mag;
-  const uint32_t neg = (over ? ~(uint32_t)smask : (uint32_t)smask) & (1u << 23);
-  cand_w = ck >= 16 ? (absv | neg) : kNoCandidate;
-  cand_i = 15 - (ck & 15);
+  const uint32_t sbit = sm & (1u << 23);
+  const uint32_t word = over ? ((2u << 23) - sbit) - mag : (mag | sbit);
+  kk.cand = rel >= 32 ? word : kNoCandidate;
+  kk.cand_bit = 0x80000000u >> (ck & 31u);
+  return A;
 }
 
-// Cold path: the SQuant-C candidate of a kernel whose perturbation sum is exactly zero
-// (nothing is masked then: the largest |p| of either sign, lowest index first).  Such a
-// kernel has k = 0, so its perturbations are those of plain rounding and are recomputed
-// here from the weights in memory.
-__device__ __noinline__ int2 k9_zero_sum_candidate(const void* w, size_t first, int wtype, float s,
-                                                   float qmaxf) {
-  int32_t best = 0, bv = 0;
+// Moves the elements named by the flip mask one step against the kernel's sign: on the
+// biased bytes a +-1 never carries into the neighbouring code.
+__device__ __forceinline__ void k9_apply_flips(K9Kernel& kk) {
+  uint32_t b0, b1, b2;
+  spread_flip_bits(kk.flips, b0, b1, b2);
+  kk.d0 -= (b0 ^ kk.sm) - kk.sm;
+  kk.d1 -= (b1 ^ kk.sm) - kk.sm;
+  kk.d2 -= (b2 ^ kk.sm) - kk.sm;
+}
+
+// Cold path for a thread that saw a kernel whose perturbation sum is exactly zero.  Nothing
+// is masked in such a kernel: its candidate is the largest |p| of either sign, lowest index
+// first.  It has k = 0, so its perturbations are those of plain rounding and are recomputed
+// here from the weights in memory; returns (sum is zero, candidate perturbation, element index).
+__device__ __noinline__ int3 k9_recheck_kernel(const void* w, size_t first, int wtype, float s, float qmaxf) {
+  int32_t best = 0, bv = 0, sum = 0;
   int bi = 0;
   for (int i = 0; i < 9; ++i) {
     float x = load_weight(w, first + i, wtype) / s;
@@ -118,9 +169,19 @@ __device__ __noinline__ int2 k9_zero_sum_candidate(const void* w, size_t first, 
     const float p = rintf(x) - x;
     const int32_t P = __float2int_rn(p * 8388608.0f);
     const int32_t ap = P < 0 ? -P : P;
+    sum += P;
     if (ap > best) { best = ap; bv = P; bi = i; }
   }
-  return make_int2(bv, bi);  // (candidate perturbation, element index)
+  return make_int3(sum == 0 ? 1 : 0, bv, bi);
+}
+
+// The candidate of a zero-sum kernel into the kernel's record: flipping it moves the element
+// against its own sign, so that sign becomes the kernel's (the flip mask is empty, so the
+// sign has had no other use).
+__device__ __forceinline__ void k9_set_zero_sum_candidate(K9Kernel& kk, int32_t v, int index) {
+  kk.cand = candidate_word(v);
+  kk.cand_bit = 1u << index;
+  kk.sm = v < 0 ? ~0u : 0u;
 }
 
 // Kernel q of a thread: nine floats at `base` (uniform, the channel's kernels q*G ...)
@@ -159,18 +220,77 @@ __device__ __forceinline__ void k9_load_kernel16(float (&w)[NW], int q, const ui
   widen_pair(u[4], bf16, w[9 * q + 8], unused);
 }
 
-template <int KPT, bool FAST, int MODE>
-__device__ __forceinline__ void k9_solve_all(const float (&w)[9 * KPT], float s, float rs, float qmaxf,
-                                             uint8_t* code8, int t, int G, int32_t& esum,
-                                             uint32_t (&cv)[KPT], int (&ci)[KPT], uint32_t& zero) {
+// Sum over the wave of values with |v| <= 2^25 (the 16 lanes of a row add up to at most 2^29).
+__device__ __forceinline__ int64_t wave_sum_rows(int32_t v) {
+  v += dpp_i32<0xB1>(v);
+  v += dpp_i32<0x4E>(v);
+  v += dpp_i32<0x141>(v);
+  v += dpp_i32<0x140>(v);
+  return (int64_t)__builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 16) +
+         __builtin_amdgcn_readlane(v, 32) + __builtin_amdgcn_readlane(v, 48);
+}
+
+// SQuant-C on the kernels a thread holds (Algorithm 2 applied to the channel; Eq. 7): among
+// the candidates with the sign of the channel sum `ec`, the round(|ec|) with the largest |v|
+// (lowest kernel index first on ties) get their flip-mask bit toggled.  Every candidate has
+// been counted into the two-sign histogram and a workgroup barrier has passed.  `list` is
+// LDS room for one dword per kernel of the channel (the place the codes go afterwards).
+// Uniform control flow: every wave scans the histogram for itself and reaches the same
+// decisions.
+template <int KPT>
+__device__ __forceinline__ void k9_channel_flip(K9Kernel (&kk)[KPT], int64_t ec, int N, int t, int G,
+                                                bool active, uint32_t* list, SelectShared& sel) {
+  const int64_t a = ec < 0 ? -ec : ec;
+  int64_t kc = flips_for(a);
+  if (kc <= 0) return;
+  if (kc > N) kc = N;
+  const uint32_t side = ec < 0 ? 256u : 0u;  // histogram half of the wanted sign
+  uint32_t need_at = 0, count_at = 0;
+  const uint32_t digit = scan_histogram_top(sel.hist + side, (uint32_t)kc, need_at, count_at);
+  // candidates of the wanted sign have bins side .. side + 255; those above bin `lo` flip
+  // at once; when fewer candidates exist than flips are wanted (no digit) all of them flip,
+  // and so do all those of bin `digit` when the count there is exactly what is still wanted
+  uint32_t lo;
+  bool rank = false;  // only some of the candidates in bin `lo` flip
+  if (digit == kNoDigit) lo = side - 1u;
+  else if (count_at == need_at) lo = side + digit - 1u;
+  else { lo = side + digit; rank = true; }
+  const uint32_t span = side + 255u - lo;
+  bool at[KPT];
 #pragma unroll
   for (int q = 0; q < KPT; ++q) {
-    float cf[9];
-    k9_solve<9 * KPT, FAST, MODE>(w, q, s, rs, qmaxf, cf, esum, cv[q], ci[q], zero);
-    const int n = t + q * G;
-#pragma unroll
-    for (int i = 0; i < 9; ++i) code8[9 * n + i] = (uint8_t)(int)cf[i];
+    const uint32_t bin = kk[q].cand >> 15;
+    const bool above = bin - lo - 1u < span;
+    at[q] = rank && active && bin == lo;
+    if (above && active) kk[q].flips ^= kk[q].cand_bit;
   }
+  if (!rank) return;
+  // Rank the candidates of bin `lo` among themselves: they agree in the top eight bits of
+  // |v|, so the low fifteen above "4095 - kernel index" order them (cin <= 4096).
+  uint32_t comp[KPT];
+#pragma unroll
+  for (int q = 0; q < KPT; ++q) {
+    comp[q] = ((kk[q].cand & 0x7FFFu) << 12) | (uint32_t)(4095 - (t + q * G));
+    if (at[q]) list[atomicAdd(&sel.list_count, 1u)] = comp[q];
+  }
+  bool any = false;
+#pragma unroll
+  for (int q = 0; q < KPT; ++q) any |= at[q];
+  __syncthreads();
+  if (__ballot(any) != 0ull) {
+    uint32_t above[KPT];
+#pragma unroll
+    for (int q = 0; q < KPT; ++q) above[q] = 0;
+    for (uint32_t e = 0; e < count_at; ++e) {
+      const uint32_t other = list[e];
+#pragma unroll
+      for (int q = 0; q < KPT; ++q) above[q] += other > comp[q] ? 1u : 0u;
+    }
+#pragma unroll
+    for (int q = 0; q < KPT; ++q)
+      if (at[q] && above[q] < need_at) kk[q].flips ^= kk[q].cand_bit;
+  }
+  __syncthreads();  // the list's place is about to take the codes
 }
 
 // One workgroup per output channel.  Thread t owns the KPT 3x3 kernels t, t + G, t + 2G, ...
@@ -210,44 +330,57 @@ __device__ __forceinline__ void k9_channel(const LaunchArgs& a, const TensorDesc
   const float s = amax > 0.0f ? amax / qmaxf : 1.0f;
   if (tid == 0) d.scales[m] = s;
 
+  K9Kernel kk[KPT];
   int32_t esum = 0;
-  uint32_t cv[KPT];
-  int ci[KPT];
+  uint32_t amin = ~0u;  // smallest |kernel sum| of this thread: 0 flags an exact-zero kernel
+  const bool fast = amax >= 0x1p-60f && amax <= 0x1p60f;  // uniform over the workgroup
+  const float rs = fast ? 1.0f / s : 0.0f;
 #pragma unroll
-  for (int q = 0; q < KPT; ++q) { cv[q] = kNoCandidate; ci[q] = 0; }
-  uint32_t zero = 0;
-  if (active) {
-    if (amax >= 0x1p-60f && amax <= 0x1p60f) {  // uniform over the workgroup
-      k9_solve_all<KPT, true, MODE>(w, s, 1.0f / s, qmaxf, code8, t, G, esum, cv, ci, zero);
-    } else {
-      k9_solve_all<KPT, false, MODE>(w, s, 0.0f, qmaxf, code8, t, G, esum, cv, ci, zero);
-    }
-    if (kChannelStage && zero != 0) {
-#pragma unroll
-      for (int q = 0; q < KPT; ++q)
-        if (zero & (1u << q)) {
-          const int2 z = k9_zero_sum_candidate(d.w, (size_t)m * L + 9 * (t + q * G), a.wtype, s, qmaxf);
-          cv[q] = candidate_word(z.x);
-          ci[q] = z.y;
-        }
+  for (int q = 0; q < KPT; ++q) {
+    uint32_t pb[9];
+    if (fast) k9_round<true>(&w[9 * q], s, rs, qmaxf, kk[q], pb);
+    else k9_round<false>(&w[9 * q], s, rs, qmaxf, kk[q], pb);
+    if (MODE != SQUANT_MODE_E) {
+      const uint32_t A = k9_flip<MODE>(pb, kk[q], esum);
+      amin = umin2(amin, A);
+      if (MODE == SQUANT_MODE_EK) k9_apply_flips(kk[q]);
     }
   }
+
   if (kChannelStage) {
+    if (amin == 0u && active) {
+#pragma unroll
+      for (int q = 0; q < KPT; ++q) {
+        const int3 z = k9_recheck_kernel(d.w, (size_t)m * L + 9 * (t + q * G), a.wtype, s, qmaxf);
+        if (z.x) k9_set_zero_sum_candidate(kk[q], z.y, z.z);
+      }
+    }
     // candidates into the histogram before the wanted sign is known: one barrier then
-    // publishes the codes, the partial sums and the histogram
+    // publishes the partial sums and the histogram
     if (active) {
 #pragma unroll
-      for (int q = 0; q < KPT; ++q) count_candidate(sh.sel, cv[q]);
+      for (int q = 0; q < KPT; ++q) count_candidate(sh.sel, kk[q].cand);
     }
-    const int64_t ec = block_sum_dpp1(esum, sh.red_i);
-    const int sgn = sign_of(ec);
-    const int64_t kc = flips_for(ec < 0 ? -ec : ec);
-    if (kc > 0) {
-      int cpos[KPT], cn[KPT];
+    // after SQuant-K a kernel's sum is at most a half; without it (mode E&C) up to 4.5
+    const int64_t ws = MODE == SQUANT_MODE_EC ? wave_sum_dpp(active ? esum : 0)
+                                              : wave_sum_rows(active ? esum : 0);
+    const int wid = tid / kWave, nw = (T + kWave - 1) / kWave;
+    if ((tid & (kWave - 1)) == 0) sh.red_i[wid] = ws;
+    __syncthreads();
+    int64_t ec = sh.red_i[0];
+    for (int i = 1; i < nw; ++i) ec += sh.red_i[i];
+    k9_channel_flip<KPT>(kk, ec, N, t, G, active, reinterpret_cast<uint32_t*>(smem), sh.sel);
 #pragma unroll
-      for (int q = 0; q < KPT; ++q) { cn[q] = t + q * G; cpos[q] = 9 * cn[q] + ci[q]; }
-      channel_stage<KPT, 1>(cv, cpos, cn, sgn, (uint32_t)(kc > N ? N : kc),
-                            reinterpret_cast<uint32_t*>(smem), sh.sel);
+    for (int q = 0; q < KPT; ++q) k9_apply_flips(kk[q]);
+  }
+
+  if (active) {
+#pragma unroll
+    for (int q = 0; q < KPT; ++q) {
+      uint8_t* dst = code8 + 9 * (t + q * G);
+      const uint64_t lo = (uint64_t)kk[q].d0 | ((uint64_t)kk[q].d1 << 32);
+      __builtin_memcpy(dst, &lo, 8);
+      dst[8] = (uint8_t)kk[q].d2;
     }
   }
   __syncthreads();
@@ -267,7 +400,7 @@ __global__ void __launch_bounds__(MAX_THREADS) squant_channel_k9(LaunchArgs a) {
 // ---------------------------------------------------------------------------
 // Depthwise 3x3 convolutions (cin per group = 1): an output channel is a single 3x3 kernel,
 // so one thread takes a whole channel - its own absmax scale, SQuant-E and SQuant-K in
-// registers through k9_solve.  SQuant-C on a one-kernel channel: after SQuant-K the
+// registers through the same routines.  SQuant-C on a one-kernel channel: after SQuant-K the
 // channel's sum is the kernel's, at most 0.5, so nothing flips (E&K&C equals E&K); without
 // SQuant-K (mode E&C) the kernel's one candidate flips when the sum rounds to 1 or more.
 // `item` is the workgroup's index within the tensor: thread t has channel item * T + t.
@@ -292,23 +425,27 @@ __device__ __forceinline__ void dw9_channels(const LaunchArgs& a, const TensorDe
   const float s = amax > 0.0f ? amax / qmaxf : 1.0f;
   d.scales[c] = s;
 
-  float cf[9];
-  int32_t esum = 0;
-  uint32_t cw = kNoCandidate, zero = 0;
-  int ci = 0;
-  k9_solve<9, false, KM>(w, 0, s, 0.0f, qmaxf, cf, esum, cw, ci, zero);
-  if (MODE == SQUANT_MODE_EC) {
-    const int32_t mag = esum < 0 ? -esum : esum;
-    if (flips_for(mag) >= 1 && cw != kNoCandidate) {
-      const float step = esum > 0 ? -1.0f : 1.0f;  // one step against the sum
-#pragma unroll
-      for (int i = 0; i < 9; ++i) cf[i] += (i == ci) ? step : 0.0f;
+  K9Kernel kk;
+  uint32_t pb[9];
+  k9_round<false>(w, s, 0.0f, qmaxf, kk, pb);
+  if (MODE != SQUANT_MODE_E) {
+    int32_t esum = 0;
+    k9_flip<KM>(pb, kk, esum);
+    if (MODE == SQUANT_MODE_EC) {
+      // the channel is this kernel: its candidate has the sign of the sum (none if the sum is 0)
+      const int32_t mag = esum < 0 ? -esum : esum;
+      if (flips_for(mag) >= 1 && kk.cand != kNoCandidate) kk.flips ^= kk.cand_bit;
     }
+    k9_apply_flips(kk);
   }
 
   int code[9];
 #pragma unroll
-  for (int i = 0; i < 9; ++i) code[i] = (int)cf[i] - 128;
+  for (int i = 0; i < 4; ++i) {
+    code[i] = (int)((kk.d0 >> (8 * i)) & 255u) - 128;
+    code[4 + i] = (int)((kk.d1 >> (8 * i)) & 255u) - 128;
+  }
+  code[8] = (int)(kk.d2 & 255u) - 128;
   if (a.out_format == SQUANT_OUT_INT8) {
     int8_t* out = static_cast<int8_t*>(d.out) + 9 * (size_t)c;
 #pragma unroll

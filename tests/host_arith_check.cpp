@@ -29,6 +29,21 @@ static long check_network() {
     squant::top5_of_9(s, top);
     for (int i = 0; i < 5; ++i) bad += top[i] != ref[i];
   }
+  for (int t = 0; t < 200000; ++t) {   // the unsigned network, keys across the sign bit
+    uint32_t s[9], ref[9], top[5];
+    for (int i = 0; i < 9; ++i) s[i] = ref[i] = (uint32_t)(xs() >> (t % 3 == 0 ? 61 : 32)) + 0x7ffffffcu;
+    std::sort(ref, ref + 9, std::greater<uint32_t>());
+    squant::top5_of_9u(s, top);
+    for (int i = 0; i < 5; ++i) bad += top[i] != ref[i];
+  }
+  for (uint32_t f = 0; f < 512; ++f) {  // flip bits to code bytes
+    uint32_t b0, b1, b2;
+    squant::spread_flip_bits(f, b0, b1, b2);
+    for (int i = 0; i < 9; ++i) {
+      const uint32_t got = i < 4 ? (b0 >> (8 * i)) & 255u : i < 8 ? (b1 >> (8 * (i - 4))) & 255u : b2;
+      bad += got != ((f >> i) & 1u);
+    }
+  }
   for (int t = 0; t < 200000; ++t) {
     int32_t s[9], ref[9];
     for (int i = 0; i < 9; ++i) s[i] = ref[i] = (int32_t)(xs() >> (t % 3 == 0 ? 60 : 33)) - (1 << 29);

@@ -63,7 +63,7 @@ def test_bad_arguments_are_rejected_on_the_host(L):
 def test_batched_argument_checks(L):
     from paper_2202_07471_amd.binding import squant_tensor_t
     assert L.squant_batched_workspace_bytes(0) == 0
-    assert L.squant_batched_workspace_bytes(3) >= 3 * 40
+    assert L.squant_batched_workspace_bytes(3) == 0      # descriptors travel in the kernel arguments
     arr = (squant_tensor_t * 2)()
     arr[0] = squant_tensor_t(0x1000, 0x2000, 0x3000, 4, 4, 3, 3)
     arr[1] = squant_tensor_t(0x1000, 0x2000, 0x3000, 4, 4, 1, 1)
@@ -73,9 +73,7 @@ def test_batched_argument_checks(L):
     assert L.squant_quantize_batched(arr, -1, 4, 2, ws, 1024, None) == 2
     assert L.squant_quantize_batched(arr, 2, 10, 2, ws, 1024, None) == 3
     assert L.squant_quantize_batched(arr, 2, 4, 9, ws, 1024, None) == 4
-    assert L.squant_quantize_batched(arr, 2, 4, 2, None, 1024, None) == 5
-    assert L.squant_quantize_batched(arr, 2, 4, 2, ws, 8, None) == 5
-    assert L.squant_quantize_batched(arr, 2, 4, 2, ctypes.c_void_p(0x4004), 1024, None) == 5
+    assert L.squant_quantize_batched(arr, 2, 4, 2, None, 1024, None) == 5   # a size without a buffer
     arr[1].codes = None
     assert L.squant_quantize_batched(arr, 2, 4, 2, ws, 1024, None) == 1
     arr[1].codes = 0x2000
@@ -126,8 +124,8 @@ def test_output_bytes_and_format_checks(L):
 def test_activation_and_network_argument_checks(L):
     from paper_2202_07471_amd.binding import squant_bn_t, squant_layer_t, squant_tensor_t
     assert L.squant_activation_workspace_bytes(0) == 0
-    assert L.squant_activation_workspace_bytes(5) >= 5 * 24
-    assert L.squant_network_workspace_bytes(5) >= L.squant_batched_workspace_bytes(5) + L.squant_activation_workspace_bytes(5)
+    assert L.squant_activation_workspace_bytes(5) == 0
+    assert L.squant_network_workspace_bytes(5) == 0
     bn = (squant_bn_t * 2)()
     bn[0] = squant_bn_t(0x1000, 0x2000, 8, 1)
     bn[1] = squant_bn_t(0x1000, 0x2000, 8, 0)
@@ -143,7 +141,6 @@ def test_activation_and_network_argument_checks(L):
     assert f(bn, 2, float("nan"), 8, out, ws, 1024, None) == 2
     assert f(bn, 2, float("inf"), 8, out, ws, 1024, None) == 2
     assert f(bn, 2, 6.0, 8, out, None, 1024, None) == 5
-    assert f(bn, 2, 6.0, 8, out, ws, 8, None) == 5
     bn[1].channels = 0
     assert f(bn, 2, 6.0, 8, out, ws, 1024, None) == 2
     bn[1].channels = 8
@@ -158,7 +155,7 @@ def test_activation_and_network_argument_checks(L):
     assert g(layers, 1, 4, 2, 1, 6.0, out, ws, 4096, None) == 3
     assert g(layers, 1, 9, 2, 8, 6.0, out, ws, 4096, None) == 3
     assert g(layers, 1, 4, 7, 8, 6.0, out, ws, 4096, None) == 4
-    assert g(layers, 1, 4, 2, 8, 6.0, out, ws, 8, None) == 5
+    assert g(layers, 1, 4, 2, 8, 6.0, out, None, 8, None) == 5
 
 
 def test_header_is_plain_c(tmp_path):
