@@ -113,6 +113,36 @@ SQ_HD void top5_of_9u(const uint32_t (&x)[9], uint32_t (&t)[5]) {
   t[4] = umax2(t2, G);
 }
 
+// The network above in two parts: the three largest (19 operations), and the next two from
+// what the first part leaves (6 operations) for the callers that need them.
+struct Top9Rest { uint32_t c, e, g, D, C; };
+SQ_HD void top3_of_9u(const uint32_t (&x)[9], uint32_t (&t)[5], Top9Rest& rest) {
+  uint32_t hi[3], mid[3], lo[3];
+#pragma unroll
+  for (int j = 0; j < 3; ++j) {
+    hi[j] = umax3(x[j], x[j + 3], x[j + 6]);
+    mid[j] = umed3(x[j], x[j + 3], x[j + 6]);
+    lo[j] = umin3(x[j], x[j + 3], x[j + 6]);
+  }
+  const uint32_t a = umax3(hi[0], hi[1], hi[2]);
+  const uint32_t b = umed3(hi[0], hi[1], hi[2]);
+  rest.c = umin3(hi[0], hi[1], hi[2]);
+  const uint32_t d = umax3(mid[0], mid[1], mid[2]);
+  rest.e = umed3(mid[0], mid[1], mid[2]);
+  rest.g = umax3(lo[0], lo[1], lo[2]);
+  rest.D = umin2(b, d);
+  rest.C = umax3(rest.c, rest.e, rest.g);
+  t[0] = a;
+  t[1] = umax2(b, d);
+  t[2] = umax2(rest.D, rest.C);
+}
+SQ_HD void next2_of_9u(const Top9Rest& rest, uint32_t (&t)[5]) {
+  const uint32_t E = umed3(rest.c, rest.e, rest.g), G = umin3(rest.c, rest.e, rest.g);
+  const uint32_t t1 = umin2(rest.D, rest.C), t2 = umin2(t1, E);
+  t[3] = umax2(t1, E);
+  t[4] = umax2(t2, G);
+}
+
 // Bits 0..8 of f (one per element of a 3x3 kernel) as 0/1 bytes in the layout of the
 // kernel's packed codes: b0 = elements 0-3, b1 = elements 4-7, b2 = element 8.  A 4-bit
 // field times 0x204081 puts bit i at positions i, i + 7, i + 14, i + 21, of which

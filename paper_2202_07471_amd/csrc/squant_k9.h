@@ -55,10 +55,33 @@ __device__ __forceinline__ uint32_t pack_low_bytes(uint32_t a, uint32_t b, uint3
   return __builtin_amdgcn_perm(b, a, 0x0c0c0400u) | __builtin_amdgcn_perm(d, c, 0x04000c0cu);
 }
 
+// Per-lane selects on lane masks held in scalar registers.  Written out because the compiler
+// otherwise turns some of the selects below into divergent branches, which cost more than
+// the one instruction and split the straight-line region the four kernels of a thread are
+// scheduled in.
+typedef uint64_t lanemask_t;
+__device__ __forceinline__ lanemask_t lanes_uge(uint32_t a, uint32_t b) { return __builtin_amdgcn_uicmp(a, b, 35); }
+__device__ __forceinline__ lanemask_t lanes_slt(int32_t a, int32_t b) { return __builtin_amdgcn_sicmp(a, b, 40); }
+__device__ __forceinline__ lanemask_t lanes_sge(int32_t a, int32_t b) { return __builtin_amdgcn_sicmp(a, b, 39); }
+__device__ __forceinline__ uint32_t vsel(lanemask_t m, uint32_t if_set, uint32_t if_clear) {
+  uint32_t r;
+  asm("v_cndmask_b32_e64 %0, %1, %2, %3" : "=v"(r) : "v"(if_clear), "v"(if_set), "s"(m));
+  return r;
+}
+
+__device__ __forceinline__ uint32_t vsel0(lanemask_t m, uint32_t if_set) {  // else 0
+  uint32_t r;
+  asm("v_cndmask_b32_e64 %0, 0, %1, %2" : "=v"(r) : "v"(if_set), "s"(m));
+  return r;
+}
+
 // SQuant-E on the nine weights w[0..8] of one kernel (Algorithm 1, rounding and element
 // perturbation): packed biased codes and the nine biased Q23 perturbations.
-//   FAST  take the quotients through the reciprocal rs = 1/s
-template <bool FAST>
+//   FAST   take the quotients through the reciprocal rs = 1/s
+//   CLAMP  clamp the quotients to [-qmax, qmax] (Section 2.2).  Only the quotient of the
+//          absmax element itself can lie outside, by one rounding of s; the caller leaves the
+//          clamp out for a channel whose absmax / s does not exceed qmax.
+template <bool FAST, bool CLAMP = true>
 __device__ __forceinline__ void k9_round(const float* w, float s, float rs, float qmaxf, K9Kernel& kk,
                                          uint32_t (&pb)[9]) {
   uint32_t tb[9];
@@ -66,7 +89,7 @@ __device__ __forceinline__ void k9_round(const float* w, float s, float rs, floa
   for (int i = 0; i < 9; ++i) {
     // x = w / s: either way the IEEE binary32 quotient
     const float x = FAST ? div_by_reciprocal(w[i], s, rs) : w[i] / s;
-    const float xc = __builtin_amdgcn_fmed3f(x, -qmaxf, qmaxf);
+    const float xc = CLAMP ? __builtin_amdgcn_fmed3f(x, -qmaxf, qmaxf) : x;
     const float t = xc + kRoundMagic;
     const float c = t - kRoundMagic;  // round-half-even(xc), exact
     const float p = c - xc;           // exact
@@ -101,7 +124,8 @@ __device__ __forceinline__ uint32_t k9_flip(const uint32_t (&pb)[9], K9Kernel& k
   uint32_t key[9];
 #pragma unroll
   for (int i = 0; i < 9; ++i) key[i] = ((pb[i] ^ sm) << 5) | (uint32_t)(31 - i);
-  const uint32_t base = sm ? ((~kQ23Bias) << 5) : (kQ23Bias << 5);
+  // base' - base = (~kQ23Bias << 5) - (kQ23Bias << 5) (mod 2^32), added for a negative sum
+  const uint32_t base = (kQ23Bias << 5) + (sm & (((~kQ23Bias) << 5) - (kQ23Bias << 5)));
 
   if (MODE == SQUANT_MODE_EC) {
     // no kernel-wise flip: k = 0, the candidate is the largest same-sign perturbation
@@ -110,7 +134,7 @@ __device__ __forceinline__ uint32_t k9_flip(const uint32_t (&pb)[9], K9Kernel& k
     const uint32_t ck = umax3(umax3(key[0], key[1], key[2]), umax3(key[3], key[4], key[5]),
                               umax3(key[6], key[7], key[8]));
     const int32_t rel = (int32_t)(ck - base);
-    kk.cand = rel >= 32 ? (((uint32_t)rel >> 5) | (sm & (1u << 23))) : kNoCandidate;
+    kk.cand = vsel(lanes_sge(rel, 32), ((uint32_t)rel >> 5) | (sm & (1u << 23)), kNoCandidate);
     kk.cand_bit = 0x80000000u >> (ck & 31u);
     return A;
   }
@@ -119,29 +143,45 @@ __device__ __forceinline__ uint32_t k9_flip(const uint32_t (&pb)[9], K9Kernel& k
   const int32_t r = (int32_t)(tt & 0x7FFFFFu) - (kHalf - 1);  // |sum| left after k flips, < 0: over SQuant
   esum += (int32_t)(((uint32_t)r ^ sm) - sm);
 
+  // The three largest keys serve every kernel with k <= 2, which is all but a few in a
+  // thousand; the rest of the network and of the selection runs only in waves that hold one.
   uint32_t srt[5];
-  top5_of_9u(key, srt);
-  const bool k1 = tt >= (1u << 23), k2 = tt >= (2u << 23), k3 = tt >= (3u << 23), k4 = tt >= (4u << 23);
+  Top9Rest rest;
+  top3_of_9u(key, srt, rest);
+  const lanemask_t k1 = lanes_uge(tt, 1u << 23), k2 = lanes_uge(tt, 2u << 23), k3 = lanes_uge(tt, 3u << 23);
   // a key's low five bits are 31 - i, so 2^31 >> key is bit i (shift counts are taken mod 32)
   const uint32_t m0 = 0x80000000u >> (srt[0] & 31u);
   const uint32_t m1 = m0 | (0x80000000u >> (srt[1] & 31u));
-  const uint32_t m2 = m1 | (0x80000000u >> (srt[2] & 31u));
-  const uint32_t m3 = m2 | (0x80000000u >> (srt[3] & 31u));
-  kk.flips = k4 ? m3 : k3 ? m2 : k2 ? m1 : k1 ? m0 : 0u;
+  uint32_t flips = vsel(k2, m1, vsel0(k1, m0));
+  uint32_t nxt = 0, thr = 0;
+  if (kCand) {
+    nxt = vsel(k2, srt[2], vsel(k1, srt[1], srt[0]));  // (k+1)-th largest
+    thr = vsel(k2, srt[1], srt[0]);                    // k-th largest, k >= 1
+  }
+  if (k3 != 0) {  // uniform over the wave
+    next2_of_9u(rest, srt);
+    const lanemask_t k4 = lanes_uge(tt, 4u << 23);
+    const uint32_t m2 = m1 | (0x80000000u >> (srt[2] & 31u));
+    const uint32_t m3 = m2 | (0x80000000u >> (srt[3] & 31u));
+    flips = vsel(k4, m3, vsel(k3, m2, flips));
+    if (kCand) {
+      nxt = vsel(k4, srt[4], vsel(k3, srt[3], nxt));
+      thr = vsel(k4, srt[3], vsel(k3, srt[2], thr));
+    }
+  }
+  kk.flips = flips;
   if (!kCand) return A;
 
   // ---- perturbation update (Algorithm 3): the kernel's candidate for SQuant-C ----
-  const bool over = r < 0;
-  const uint32_t nxt = k4 ? srt[4] : k3 ? srt[3] : k2 ? srt[2] : k1 ? srt[1] : srt[0];  // (k+1)-th
-  const uint32_t thr = k4 ? srt[3] : k3 ? srt[2] : k2 ? srt[1] : srt[0];                // k-th, k >= 1
-  const uint32_t ck = over ? thr : nxt;  // over: last flipped; under: first un-flipped
+  const lanemask_t over = lanes_slt(r, 0);
+  const uint32_t ck = vsel(over, thr, nxt);  // over: last flipped; under: first un-flipped
   const int32_t rel = (int32_t)(ck - base);         // 32 |p| + (31 - i) for a same-sign element
   const uint32_t mag = (uint32_t)rel >> 5;          // |p| of that element before any flip
   // over: the post-flip value kOne - mag with the sign opposite to the sum; under: mag with
   // the sign of the sum
   const uint32_t sbit = sm & (1u << 23);
-  const uint32_t word = over ? ((2u << 23) - sbit) - mag : (mag | sbit);
-  kk.cand = rel >= 32 ? word : kNoCandidate;
+  const uint32_t word = vsel(over, ((2u << 23) - sbit) - mag, mag | sbit);
+  kk.cand = vsel(lanes_sge(rel, 32), word, kNoCandidate);
   kk.cand_bit = 0x80000000u >> (ck & 31u);
   return A;
 }
@@ -156,13 +196,14 @@ __device__ __forceinline__ void k9_apply_flips(K9Kernel& kk) {
   kk.d2 -= (b2 ^ kk.sm) - kk.sm;
 }
 
-// Cold path for a thread that saw a kernel whose perturbation sum is exactly zero.  Nothing
+// Cold path (a rolled loop) for a thread that saw a kernel whose perturbation sum is exactly zero.  Nothing
 // is masked in such a kernel: its candidate is the largest |p| of either sign, lowest index
 // first.  It has k = 0, so its perturbations are those of plain rounding and are recomputed
 // here from the weights in memory; returns (sum is zero, candidate perturbation, element index).
-__device__ __noinline__ int3 k9_recheck_kernel(const void* w, size_t first, int wtype, float s, float qmaxf) {
+__device__ __forceinline__ int3 k9_recheck_kernel(const void* w, size_t first, int wtype, float s, float qmaxf) {
   int32_t best = 0, bv = 0, sum = 0;
   int bi = 0;
+#pragma unroll 1
   for (int i = 0; i < 9; ++i) {
     float x = load_weight(w, first + i, wtype) / s;
     x = fminf(fmaxf(x, -qmaxf), qmaxf);
@@ -293,6 +334,36 @@ __device__ __forceinline__ void k9_channel_flip(K9Kernel (&kk)[KPT], int64_t ec,
   __syncthreads();  // the list's place is about to take the codes
 }
 
+// SQuant-E and SQuant-K on all the kernels of a thread.
+//   PRESCALE  the weights are first multiplied by the powers of two f1 and f2 (and s, rs are
+//             those of the scaled channel): see k9_channel
+template <int MODE, int KPT, bool PRESCALE, bool CLAMP>
+__device__ __forceinline__ void k9_solve_all(const float (&w)[9 * KPT], float s, float rs, float qmaxf,
+                                             float f1, float f2, K9Kernel (&kk)[KPT], int32_t& esum,
+                                             uint32_t& amin) {
+#pragma unroll
+  for (int q = 0; q < KPT; ++q) {
+    // A branch that is always taken (s is finite) but that the compiler cannot fold: it makes
+    // every kernel a basic block of its own, which keeps the scheduler from interleaving the
+    // kernels (that costs 118 instead of about 90 registers) at the price of two scalar
+    // instructions.
+    kk[q].d0 = kk[q].d1 = kk[q].d2 = kk[q].flips = kk[q].sm = kk[q].cand_bit = 0;
+    kk[q].cand = kNoCandidate;
+    if (__float_as_uint(s) + (uint32_t)q == 0xFFFFFFF0u) continue;
+    float x[9];
+#pragma unroll
+    for (int i = 0; i < 9; ++i) {
+      x[i] = PRESCALE ? w[9 * q + i] * f1 * f2 : w[9 * q + i];
+    }
+    uint32_t pb[9];
+    k9_round<true, CLAMP>(x, s, rs, qmaxf, kk[q], pb);
+    if (MODE != SQUANT_MODE_E) {
+      amin = umin2(amin, k9_flip<MODE>(pb, kk[q], esum));
+      if (MODE == SQUANT_MODE_EK) k9_apply_flips(kk[q]);
+    }
+  }
+}
+
 // One workgroup per output channel.  Thread t owns the KPT 3x3 kernels t, t + G, t + 2G, ...
 // (G = cin / KPT); KPT is 4 for wide layers and 2 or 1 for narrow ones, so that the waves
 // stay full.
@@ -333,18 +404,23 @@ __device__ __forceinline__ void k9_channel(const LaunchArgs& a, const TensorDesc
   K9Kernel kk[KPT];
   int32_t esum = 0;
   uint32_t amin = ~0u;  // smallest |kernel sum| of this thread: 0 flags an exact-zero kernel
-  const bool fast = amax >= 0x1p-60f && amax <= 0x1p60f;  // uniform over the workgroup
-  const float rs = fast ? 1.0f / s : 0.0f;
-#pragma unroll
-  for (int q = 0; q < KPT; ++q) {
-    uint32_t pb[9];
-    if (fast) k9_round<true>(&w[9 * q], s, rs, qmaxf, kk[q], pb);
-    else k9_round<false>(&w[9 * q], s, rs, qmaxf, kk[q], pb);
-    if (MODE != SQUANT_MODE_E) {
-      const uint32_t A = k9_flip<MODE>(pb, kk[q], esum);
-      amin = umin2(amin, A);
-      if (MODE == SQUANT_MODE_EK) k9_apply_flips(kk[q]);
-    }
+  // The quotients w / s go through the reciprocal of s, which is proven exact while nothing
+  // under- or overflows on the way: absmax within [2^-60, 2^60].  A channel outside that range
+  // is first scaled by a power of two, weights and scale alike (exact, and the quotients are
+  // those of the unscaled channel; an element that leaves the normal range on the way down is
+  // more than 2^60 below the absmax and rounds to code 0 with perturbation 0 either way).
+  // One uniform branch around all the kernels of the thread, each side one straight-line region.
+  if (amax <= 0x1p60f && (amax >= 0x1p-60f || amax == 0.0f)) {
+    const float rs = 1.0f / s;
+    // the largest quotient of the channel: no element needs the clamp unless this one does
+    if (div_by_reciprocal(amax, s, rs) <= qmaxf) k9_solve_all<MODE, KPT, false, false>(w, s, rs, qmaxf, 1.0f, 1.0f, kk, esum, amin);
+    else k9_solve_all<MODE, KPT, false, true>(w, s, rs, qmaxf, 1.0f, 1.0f, kk, esum, amin);
+  } else {
+    const float f1 = amax < 1.0f ? 0x1p64f : 0x1p-64f;
+    const float a1 = amax * f1;
+    const float f2 = a1 < 0x1p-60f ? 0x1p64f : a1 > 0x1p60f ? 0x1p-64f : 1.0f;
+    const float s2 = s * f1 * f2;
+    k9_solve_all<MODE, KPT, true, true>(w, s2, 1.0f / s2, qmaxf, f1, f2, kk, esum, amin);
   }
 
   if (kChannelStage) {
@@ -388,8 +464,11 @@ __device__ __forceinline__ void k9_channel(const LaunchArgs& a, const TensorDesc
   emit_channel(reinterpret_cast<const uint32_t*>(smem), nvec, d.out, m, s, a.out_format, tid, T);
 }
 
+// Compiled for five waves per SIMD (at most 102 VGPRs): left alone, the scheduler interleaves
+// the four kernels of a thread further than the register file pays for.
 template <int MAX_THREADS, int MODE, int KPT>
-__global__ void __launch_bounds__(MAX_THREADS) squant_channel_k9(LaunchArgs a) {
+__global__ void __launch_bounds__(MAX_THREADS) __attribute__((amdgpu_waves_per_eu(5)))
+    squant_channel_k9(LaunchArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];  // 9*N bytes of codes
   __shared__ K9Shared sh;
   int m;

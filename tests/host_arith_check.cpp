@@ -35,6 +35,23 @@ static long check_network() {
     std::sort(ref, ref + 9, std::greater<uint32_t>());
     squant::top5_of_9u(s, top);
     for (int i = 0; i < 5; ++i) bad += top[i] != ref[i];
+    uint32_t two[5];
+    squant::Top9Rest rest;
+    squant::top3_of_9u(s, two, rest);
+    squant::next2_of_9u(rest, two);
+    for (int i = 0; i < 5; ++i) bad += two[i] != ref[i];
+  }
+  for (int bits = 0; bits < 512; ++bits) {   // the two-part network on every 0/1 input
+    uint32_t s[9], ref[9], two[5];
+    for (int i = 0; i < 9; ++i) s[i] = ref[i] = (bits >> i) & 1;
+    std::sort(ref, ref + 9, std::greater<uint32_t>());
+    squant::Top9Rest rest;
+    squant::top3_of_9u(s, two, rest);
+    squant::next2_of_9u(rest, two);
+    for (int i = 0; i < 5; ++i) bad += two[i] != ref[i];
+    uint32_t top[5];
+    squant::top5_of_9u(s, top);
+    for (int i = 0; i < 5; ++i) bad += top[i] != ref[i];
   }
   for (uint32_t f = 0; f < 512; ++f) {  // flip bits to code bytes
     uint32_t b0, b1, b2;
