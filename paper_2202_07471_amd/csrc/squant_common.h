@@ -32,6 +32,7 @@ struct LaunchArgs {
   int32_t n_tensors;        // descriptors in `table`, ordered by `first`
   int32_t total;            // workgroups in this launch (one per output channel, except depthwise)
   int32_t uniform_m;        // > 0: every tensor of the table takes this many workgroups
+  int32_t uniform_shift;    // >= 0: uniform_m == 1 << uniform_shift
   int32_t qmax;
   int32_t mode;
   int32_t out_format;       // squant_output_t
@@ -58,7 +59,9 @@ __device__ __forceinline__ TensorDesc locate(const LaunchArgs& a, int g, int& m)
   }
   int t = 0;
   if (a.n_tensors > 1) {
-    if (a.uniform_m > 0) {
+    if (a.uniform_shift >= 0) {
+      t = g >> a.uniform_shift;
+    } else if (a.uniform_m > 0) {
       t = g / a.uniform_m;
     } else {
       // last t with first[t] <= g.  The offsets ascend, so t + 1 is the number of tensors whose
@@ -122,17 +125,19 @@ __device__ __forceinline__ float dpp_f32(float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
 }
 
-// max over the wave of non-negative floats; uniform result
+// max over the wave of non-negative floats; uniform result.  The bit patterns of non-negative
+// floats order like unsigned integers, and the integer maximum folds into the DPP move.
 __device__ __forceinline__ float wave_max_dpp(float v) {
-  v = fmaxf(v, dpp_f32<0xB1>(v));
-  v = fmaxf(v, dpp_f32<0x4E>(v));
-  v = fmaxf(v, dpp_f32<0x141>(v));
-  v = fmaxf(v, dpp_f32<0x140>(v));
-  const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
-  const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
-  const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
-  const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
-  return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
+  uint32_t u = __float_as_uint(v);
+  u = max(u, (uint32_t)dpp_i32<0xB1>((int)u));
+  u = max(u, (uint32_t)dpp_i32<0x4E>((int)u));
+  u = max(u, (uint32_t)dpp_i32<0x141>((int)u));
+  u = max(u, (uint32_t)dpp_i32<0x140>((int)u));
+  const uint32_t r0 = (uint32_t)__builtin_amdgcn_readlane((int)u, 0);
+  const uint32_t r1 = (uint32_t)__builtin_amdgcn_readlane((int)u, 16);
+  const uint32_t r2 = (uint32_t)__builtin_amdgcn_readlane((int)u, 32);
+  const uint32_t r3 = (uint32_t)__builtin_amdgcn_readlane((int)u, 48);
+  return __uint_as_float(max(max(r0, r1), max(r2, r3)));
 }
 
 // sum over the wave of any int32 values; uniform 64-bit result.  The low 16 bits (unsigned) and

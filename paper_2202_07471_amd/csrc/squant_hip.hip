@@ -212,6 +212,10 @@ int launch_part(const Group& g, size_t begin, size_t end, int qmax, int mode, in
   a.n_tensors = (int)(end - begin);
   a.total = (int32_t)total;
   a.uniform_m = uniform ? (int32_t)items0 : 0;
+  a.uniform_shift = -1;
+  if (uniform && (items0 & (items0 - 1)) == 0)
+    for (int sh = 0; sh < 31; ++sh)
+      if (((int64_t)1 << sh) == items0) a.uniform_shift = sh;
   a.qmax = qmax;
   a.mode = mode;
   a.out_format = output;
@@ -224,6 +228,15 @@ int launch_part(const Group& g, size_t begin, size_t end, int qmax, int mode, in
   static const kernel_t k9x4[4] = SQ_K9_ROW(256, 4);
   static const kernel_t k9x4_large[4] = SQ_K9_ROW(1024, 4);
 #undef SQ_K9_ROW
+  // four kernels per thread in workgroups of exactly two waves (cin 260 .. 512) or one
+  // (cin 152 .. 256): weight type and wave count compiled in
+#define SQ_K9_ROW_X(WT, NWC)                                                                  \
+  {squant_channel_k9<256, SQUANT_MODE_E, 4, WT, NWC>, squant_channel_k9<256, SQUANT_MODE_EK, 4, WT, NWC>, \
+   squant_channel_k9<256, SQUANT_MODE_EKC, 4, WT, NWC>, squant_channel_k9<256, SQUANT_MODE_EC, 4, WT, NWC>}
+  static const kernel_t k9x4_two_waves[3][4] = {SQ_K9_ROW_X(SQUANT_W_F32, 2), SQ_K9_ROW_X(SQUANT_W_F16, 2),
+                                                SQ_K9_ROW_X(SQUANT_W_BF16, 2)};
+  static const kernel_t k9x4_one_wave[4] = SQ_K9_ROW_X(SQUANT_W_F32, 1);
+#undef SQ_K9_ROW_X
 #define SQ_K1_ROW(T, NV)                                                                      \
   {squant_channel_k1<T, SQUANT_MODE_E, NV>, squant_channel_k1<T, SQUANT_MODE_E, NV>,          \
    squant_channel_k1<T, SQUANT_MODE_EKC, NV>, squant_channel_k1<T, SQUANT_MODE_EKC, NV>}
@@ -267,7 +280,9 @@ int launch_part(const Group& g, size_t begin, size_t end, int qmax, int mode, in
                           : g.variant == kK1Team ? k1team[mode]
                           : g.variant == kK9x1 ? k9x1[mode]
                           : g.variant == kK9x2 ? k9x2[mode]
-                          : g.variant == kK9x4 ? (g.threads <= 256 ? k9x4[mode] : k9x4_large[mode])
+                          : g.variant == kK9x4 ? (g.threads == 2 * kWave ? k9x4_two_waves[wtype][mode]
+                                                  : g.threads == kWave && wtype == SQUANT_W_F32 ? k9x4_one_wave[mode]
+                                                  : g.threads <= 256 ? k9x4[mode] : k9x4_large[mode])
                                                : squant_channel_generic;
   if (!kernel) return SQUANT_ERR_UNSUPPORTED;
   if (g.lds > 48 * 1024) {

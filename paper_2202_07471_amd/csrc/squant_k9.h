@@ -271,6 +271,46 @@ __device__ __forceinline__ int64_t wave_sum_rows(int32_t v) {
          __builtin_amdgcn_readlane(v, 32) + __builtin_amdgcn_readlane(v, 48);
 }
 
+// Workgroup-wide maximum / sum with the number of waves known at compile time (NWC = 0: taken
+// from the launch).  One barrier each (none for a one-wave workgroup), for callers that pass
+// another barrier before they use the same slots again.
+template <int NWC>
+__device__ __forceinline__ float k9_block_max(float v, float* slot) {
+  if (NWC == 0) return block_max_dpp1(v, slot);
+  v = wave_max_dpp(v);
+  if (NWC == 1) return v;
+  if ((threadIdx.x & (kWave - 1)) == 0) slot[threadIdx.x / kWave] = v;
+  __syncthreads();
+  float r = slot[0];
+#pragma unroll
+  for (int i = 1; i < NWC; ++i) r = fmaxf(r, slot[i]);
+  return r;
+}
+template <int NWC>
+__device__ __forceinline__ int64_t k9_block_sum(int64_t ws, int64_t* slot) {
+  if (NWC == 1) return ws;
+  const int nw = NWC ? NWC : (int)((blockDim.x + kWave - 1) / kWave);
+  if ((threadIdx.x & (kWave - 1)) == 0) slot[threadIdx.x / kWave] = ws;
+  __syncthreads();
+  int64_t r = slot[0];
+  if (NWC) {
+#pragma unroll
+    for (int i = 1; i < NWC; ++i) r += slot[i];
+  } else {
+    for (int i = 1; i < nw; ++i) r += slot[i];
+  }
+  return r;
+}
+// Zeroes the histogram and the list counter (132 sixteen-byte stores and one more).
+template <int NWC>
+__device__ __forceinline__ void k9_select_reset(SelectShared& sel) {
+  if (NWC == 0) { select_reset(sel); return; }
+#pragma unroll
+  for (int b = 0; b < 132; b += kWave * NWC)
+    if (b + (int)threadIdx.x < 132) reinterpret_cast<uint4*>(sel.hist)[b + threadIdx.x] = make_uint4(0, 0, 0, 0);
+  if (threadIdx.x == 0) sel.list_count = 0;
+}
+
 // SQuant-C on the kernels a thread holds (Algorithm 2 applied to the channel; Eq. 7): among
 // the candidates with the sign of the channel sum `ec`, the round(|ec|) with the largest |v|
 // (lowest kernel index first on ties) get their flip-mask bit toggled.  Every candidate has
@@ -367,11 +407,14 @@ __device__ __forceinline__ void k9_solve_all(const float (&w)[9 * KPT], float s,
 // One workgroup per output channel.  Thread t owns the KPT 3x3 kernels t, t + G, t + 2G, ...
 // (G = cin / KPT); KPT is 4 for wide layers and 2 or 1 for narrow ones, so that the waves
 // stay full.
-template <int MODE, int KPT>
+//   WT   the weight type when it is known at compile time (squant_wtype_t), -1: the launch's
+//   NWC  the waves per workgroup when known at compile time, 0: the launch's
+template <int MODE, int KPT, int WT = -1, int NWC = 0>
 __device__ __forceinline__ void k9_channel(const LaunchArgs& a, const TensorDesc& d, int m,
                                            unsigned char* smem, K9Shared& sh) {
   constexpr bool kChannelStage = MODE == SQUANT_MODE_EKC || MODE == SQUANT_MODE_EC;
-  const int T = blockDim.x, tid = threadIdx.x;
+  const int T = NWC ? NWC * kWave : (int)blockDim.x, tid = threadIdx.x;
+  const int wtype = WT >= 0 ? WT : a.wtype;
   const float qmaxf = (float)a.qmax;
   uint8_t* code8 = reinterpret_cast<uint8_t*>(smem);  // biased codes: code + 128
 
@@ -380,24 +423,24 @@ __device__ __forceinline__ void k9_channel(const LaunchArgs& a, const TensorDesc
   const bool active = tid < G;
   const int t = active ? tid : 0;  // idle threads shadow thread 0's loads and write nothing
   float w[9 * KPT];
-  if (a.wtype == SQUANT_W_F32) {
+  if (wtype == SQUANT_W_F32) {
     const float* src = static_cast<const float*>(d.w) + (size_t)m * L;
 #pragma unroll
     for (int q = 0; q < KPT; ++q) k9_load_kernel(w, q, src + (size_t)q * (9 * G), 9u * (uint32_t)t);
   } else {
     const uint32_t* chan32 =
         reinterpret_cast<const uint32_t*>(static_cast<const uint16_t*>(d.w) + (size_t)m * L);
-    const bool bf16 = a.wtype == SQUANT_W_BF16;
+    const bool bf16 = wtype == SQUANT_W_BF16;
 #pragma unroll
     for (int q = 0; q < KPT; ++q) k9_load_kernel16(w, q, chan32, (uint32_t)(t + q * G), bf16);
   }
-  if (kChannelStage) select_reset(sh.sel);  // before the first barrier
+  if (kChannelStage) k9_select_reset<NWC>(sh.sel);  // before the first barrier
 
   float amax = 0.0f;
 #pragma unroll
   for (int j = 0; j + 1 < 9 * KPT; j += 2) amax = fmaxf(fmaxf(amax, fabsf(w[j])), fabsf(w[j + 1]));
   if ((9 * KPT) & 1) amax = fmaxf(amax, fabsf(w[9 * KPT - 1]));
-  amax = block_max_dpp1(amax, sh.red_f);
+  amax = k9_block_max<NWC>(amax, sh.red_f);
   const float s = amax > 0.0f ? amax / qmaxf : 1.0f;
   if (tid == 0) d.scales[m] = s;
 
@@ -427,7 +470,7 @@ __device__ __forceinline__ void k9_channel(const LaunchArgs& a, const TensorDesc
     if (amin == 0u && active) {
 #pragma unroll
       for (int q = 0; q < KPT; ++q) {
-        const int3 z = k9_recheck_kernel(d.w, (size_t)m * L + 9 * (t + q * G), a.wtype, s, qmaxf);
+        const int3 z = k9_recheck_kernel(d.w, (size_t)m * L + 9 * (t + q * G), wtype, s, qmaxf);
         if (z.x) k9_set_zero_sum_candidate(kk[q], z.y, z.z);
       }
     }
@@ -440,11 +483,7 @@ __device__ __forceinline__ void k9_channel(const LaunchArgs& a, const TensorDesc
     // after SQuant-K a kernel's sum is at most a half; without it (mode E&C) up to 4.5
     const int64_t ws = MODE == SQUANT_MODE_EC ? wave_sum_dpp(active ? esum : 0)
                                               : wave_sum_rows(active ? esum : 0);
-    const int wid = tid / kWave, nw = (T + kWave - 1) / kWave;
-    if ((tid & (kWave - 1)) == 0) sh.red_i[wid] = ws;
-    __syncthreads();
-    int64_t ec = sh.red_i[0];
-    for (int i = 1; i < nw; ++i) ec += sh.red_i[i];
+    const int64_t ec = k9_block_sum<NWC>(ws, sh.red_i);
     k9_channel_flip<KPT>(kk, ec, N, t, G, active, reinterpret_cast<uint32_t*>(smem), sh.sel);
 #pragma unroll
     for (int q = 0; q < KPT; ++q) k9_apply_flips(kk[q]);
@@ -466,14 +505,14 @@ __device__ __forceinline__ void k9_channel(const LaunchArgs& a, const TensorDesc
 
 // Compiled for five waves per SIMD (at most 102 VGPRs): left alone, the scheduler interleaves
 // the four kernels of a thread further than the register file pays for.
-template <int MAX_THREADS, int MODE, int KPT>
+template <int MAX_THREADS, int MODE, int KPT, int WT = -1, int NWC = 0>
 __global__ void __launch_bounds__(MAX_THREADS) __attribute__((amdgpu_waves_per_eu(5)))
     squant_channel_k9(LaunchArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];  // 9*N bytes of codes
   __shared__ K9Shared sh;
   int m;
   const TensorDesc d = locate(a, blockIdx.x, m);
-  k9_channel<MODE, KPT>(a, d, m, smem, sh);
+  k9_channel<MODE, KPT, WT, NWC>(a, d, m, smem, sh);
 }
 
 // ---------------------------------------------------------------------------
