@@ -65,7 +65,7 @@ typedef enum {
   SQUANT_ERR_MODE = 4,      /* unknown mode */
   SQUANT_ERR_WORKSPACE = 5, /* a workspace size without a workspace pointer */
   SQUANT_ERR_DEVICE = 6,    /* a HIP call failed */
-  SQUANT_ERR_UNSUPPORTED = 7, /* one output channel (cin*kh*kw) exceeds what one workgroup's LDS holds */
+  SQUANT_ERR_UNSUPPORTED = 7, /* not returned by this version: every channel within the shape limits is taken */
   SQUANT_ERR_FORMAT = 8     /* unknown weight or output type, or a buffer misaligned for its element type */
 } squant_status_t;
 
@@ -196,9 +196,11 @@ int squant_quantize_network(const squant_layer_t* h_layers, int32_t n_layers, in
                             squant_act_range_t* d_ranges, void* d_workspace,
                             size_t workspace_bytes, void* stream);
 
-/* Largest cin*kh*kw one output channel may have (device dependent; 0 on error).  The figure
- * is for 16-byte aligned weights with cin a multiple of 4; for 1x1 and 3x3 kernels other
- * tensors go through the generic kernel, which holds more per element and takes less. */
+/* Largest cin*kh*kw one output channel may have: 2^30, the bound of the shape check (0 for an
+ * invalid kernel size).  Channels that fit none of the kernels which keep a channel on chip
+ * (3x3 beyond cin 4096, other kernel sizes beyond about 32 K elements, 1x1 / FC rows beyond
+ * about 160 K elements or off 16-byte alignment beyond 13 K) go through a streaming kernel
+ * that walks the weights several times: correct for any shape, a fraction of the speed. */
 int64_t squant_max_channel_elems(int32_t kh, int32_t kw);
 
 const char* squant_status_string(int status);

@@ -26,6 +26,7 @@
 #include "squant_ks.h"
 #include "squant_k1.h"
 #include "squant_mixed.h"
+#include "squant_stream.h"
 #include "squant_act.h"
 #include "squant_plan.h"
 
@@ -107,7 +108,13 @@ struct Plan { int variant; int threads; size_t lds; int mix_threads; };
 
 inline size_t round_up(size_t v, size_t to) { return (v + to - 1) / to * to; }
 
-// Picks the kernel variant and launch shape for one tensor; lds = 0 means it fits none.
+// The fallback that takes any channel: nothing is kept on chip.
+Plan stream_plan(int64_t N) {
+  const int th = (int)std::min<int64_t>(kStreamThreads, std::max<int64_t>(2 * kWave, round_up64(N)));
+  return Plan{kStream, th, 16, 0};  // no dynamic LDS; 16 stands for "fits"
+}
+
+// Picks the kernel variant and launch shape for one tensor (every tensor fits one).
 Plan plan_tensor(const void* w, const void* out, int64_t N, int64_t K, int lds_limit) {
   const int variant = choose_variant(N, K, pointers_aligned(w, out));
   switch (variant) {
@@ -129,7 +136,7 @@ Plan plan_tensor(const void* w, const void* out, int64_t N, int64_t K, int lds_l
     case kK1Team: return Plan{kK1Team, kWave, 16, kWave};
     case kK1Stream: {
       const size_t lds = round_up((size_t)N, 16);  // the channel's int8 codes
-      if (lds + sizeof(K9Shared) + 64 > (size_t)lds_limit) return Plan{kK1Stream, 0, 0, 0};
+      if (lds + sizeof(K9Shared) + 64 > (size_t)lds_limit) return stream_plan(N);
       return Plan{kK1Stream, 1024, lds, 0};
     }
     default: break;
@@ -137,7 +144,7 @@ Plan plan_tensor(const void* w, const void* out, int64_t N, int64_t K, int lds_l
   if (is_ks(variant))  // LDS: the channel's int8 codes
     return Plan{variant, (int)round_up64(N / ks_variant_kpt(variant)), round_up((size_t)K * N, 16), 0};
   const size_t lds = generic_lds_bytes(N, K);
-  if (lds + kStaticLds > (size_t)lds_limit) return Plan{kGeneric, 0, 0, 0};
+  if (lds + kStaticLds > (size_t)lds_limit) return stream_plan(N);
   const int th = generic_threads(N, K);
   return Plan{kGeneric, th, lds, th};
 }
@@ -256,6 +263,8 @@ int launch_part(const Group& g, size_t begin, size_t end, int qmax, int mode, in
 #undef SQ_K1_ROW
   static const kernel_t k1s[4] = {squant_channel_k1_stream<SQUANT_MODE_E>, squant_channel_k1_stream<SQUANT_MODE_E>,
                                   squant_channel_k1_stream<SQUANT_MODE_EKC>, squant_channel_k1_stream<SQUANT_MODE_EKC>};
+  static const kernel_t stream[4] = {squant_channel_stream<SQUANT_MODE_E>, squant_channel_stream<SQUANT_MODE_EK>,
+                                     squant_channel_stream<SQUANT_MODE_EKC>, squant_channel_stream<SQUANT_MODE_EC>};
   static const kernel_t k1team[4] = {squant_channel_k1_team<SQUANT_MODE_E>, squant_channel_k1_team<SQUANT_MODE_E>,
                                      squant_channel_k1_team<SQUANT_MODE_EKC>, squant_channel_k1_team<SQUANT_MODE_EKC>};
   static const kernel_t dw9[4] = {squant_channel_dw9<SQUANT_MODE_E>, squant_channel_dw9<SQUANT_MODE_EK>,
@@ -276,6 +285,7 @@ int launch_part(const Group& g, size_t begin, size_t end, int qmax, int mode, in
                           : g.variant == kK1x7 ? k1x7[mode]
                           : g.variant == kK1x8 ? (g.threads <= 256 ? k1x8_small[mode] : g.threads <= 768 ? k1x8_mid[mode] : k1x8[mode])
                           : g.variant == kK1Stream ? k1s[mode]
+                          : g.variant == kStream ? stream[mode]
                           : g.variant == kDw9 ? dw9[mode]
                           : g.variant == kK1Team ? k1team[mode]
                           : g.variant == kK9x1 ? k9x1[mode]
@@ -293,7 +303,7 @@ int launch_part(const Group& g, size_t begin, size_t end, int qmax, int mode, in
     }
   }
   const unsigned grid = (unsigned)total;
-  hipLaunchKernelGGL(kernel, dim3(grid), dim3(g.threads), g.lds, st, a);
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(g.threads), g.variant == kStream ? 0 : g.lds, st, a);
   if (hipGetLastError() != hipSuccess) return SQUANT_ERR_DEVICE;
   return SQUANT_OK;
 }
@@ -533,19 +543,8 @@ int squant_quantize_network(const squant_layer_t* h_layers, int32_t n_layers, in
 }
 
 int64_t squant_max_channel_elems(int32_t kh, int32_t kw) {
-  if (kh <= 0 || kw <= 0) return 0;
-  const DeviceLimits lim = device_limits();
-  if (!lim.ok) { (void)hipGetLastError(); return 0; }
-  const int64_t K = (int64_t)kh * kw;
-  // largest N with generic_lds_bytes(N, K) + static <= limit
-  const int64_t budget = (int64_t)lim.lds_bytes - kStaticLds - 16 - 3;
-  const int64_t per_kernel = 5 * K + (K == 1 ? 0 : 8);
-  int64_t n = budget / per_kernel;
-  if (n < 0) n = 0;
-  // the specialised kernels (16-byte aligned weights, cin a multiple of 4) hold less per element
-  if (K == 9) n = std::max<int64_t>(n, kMaxK9Cin);
-  if (K == 1) n = std::max<int64_t>(n, ((int64_t)lim.lds_bytes - (int64_t)sizeof(K9Shared) - 64) / 16 * 16);
-  return n * K;
+  if (kh <= 0 || kw <= 0 || (int64_t)kh * kw > (1 << 20)) return 0;
+  return (int64_t)1 << 30;  // the bound of the argument check: the streaming kernel takes any channel
 }
 
 const char* squant_status_string(int status) {
@@ -557,7 +556,7 @@ const char* squant_status_string(int status) {
     case SQUANT_ERR_MODE: return "unknown mode";
     case SQUANT_ERR_WORKSPACE: return "workspace size given without a workspace";
     case SQUANT_ERR_DEVICE: return "HIP call failed";
-    case SQUANT_ERR_UNSUPPORTED: return "output channel too large for one workgroup's LDS";
+    case SQUANT_ERR_UNSUPPORTED: return "unsupported (not returned by this version)";
     case SQUANT_ERR_FORMAT: return "unknown weight or output type, or misaligned buffer";
     default: return "unknown status";
   }

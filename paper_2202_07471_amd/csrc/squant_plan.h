@@ -17,6 +17,7 @@ enum Variant {
   kDw9 = 9,                                    // depthwise 3x3 (cin per group = 1): one thread per channel
   kK1Team = 10,                                // 1x1 / FC up to kMaxTeamCin: 4 to 16 channels per wave
   kK1x3 = 11, kK1x5 = 12, kK1x6 = 13, kK1x7 = 14,  // 1x1 / FC: 3, 5, 6, 7 vectors per thread
+  kStream = 15,                                // any shape: nothing kept on chip, weights walked repeatedly
   kKs = 1024                                   // small kernels in registers: kKs + 4 * K + log2(kernels per thread)
 };
 
