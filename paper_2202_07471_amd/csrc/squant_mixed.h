@@ -15,12 +15,12 @@ namespace squant {
 
 constexpr int kMixedMaxThreads = 256;
 
-// Compiled for six waves per SIMD (80 VGPRs; the four-kernel 3x3 routine alone would take 92):
+// Compiled for five waves per SIMD (at most 96 VGPRs, what the four-kernel 3x3 routine needs):
 // these launches live on the number of resident workgroups.  Measured 2-4 % faster on the
 // ResNet-50 and MobileNetV2 sets; eight waves spill in the 3x3 routine and cost ResNet-18 24 %.
 template <int MODE>
 __global__ void __launch_bounds__(kMixedMaxThreads)
-    __attribute__((amdgpu_waves_per_eu(6))) squant_channel_mixed(LaunchArgs a) {
+    __attribute__((amdgpu_waves_per_eu(5))) squant_channel_mixed(LaunchArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ K9Shared sh;
   __shared__ GenericShared gs;

@@ -20,10 +20,7 @@
 namespace squant {
 
 constexpr int kListCap = 128;  // capacity of the ranking list
-#ifndef SQ_TUNE_LIST_RANK
-#define SQ_TUNE_LIST_RANK 16
-#endif
-constexpr int kListRank = SQ_TUNE_LIST_RANK;  // rank through the list up to this many keys; above
+constexpr int kListRank = 16;  // rank through the list up to this many keys; above
                                               // it another histogram pass is cheaper than the
                                               // quadratic ranking
 constexpr int kHistDummy = 512;  // bin of "no candidate"
