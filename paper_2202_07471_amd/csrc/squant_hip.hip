@@ -124,13 +124,17 @@ Plan plan_tensor(const void* w, const void* out, int64_t N, int64_t K, int lds_l
       const int th = (int)round_up64(N / kpt);
       return Plan{variant, th, round_up((size_t)9 * N, 16), th};
     }
-    case kK1x1: case kK1x2: case kK1x3: case kK1x4: case kK1x5: case kK1x6: case kK1x7: case kK1x8: {
+    case kK1x1: case kK1x2: case kK1x3: case kK1x4: case kK1x5: case kK1x6: case kK1x7: case kK1x8:
+    case kK1x16: {
       const int nv = k1_variant_nv(variant);
       const int64_t nvec = N / 4;
       const int th = (int)k1_threads(nvec, nv);
       // the mixed kernel carries the routines of up to four vectors per thread
       const int mix = nv <= 4 ? th : nvec <= 4 * kMixedMaxThreads ? (int)round_up64((nvec + 3) / 4) : 0;
-      return Plan{variant, th, round_up((size_t)N, 16), mix};
+      // LDS: the owners' masks, a word per thread (of the launch's workgroup, which a mixed
+      // launch may make larger), two with sixteen vectors
+      const size_t lds = nv > 8 ? (size_t)8 * th : (size_t)4 * std::max(th, kMixedMaxThreads);
+      return Plan{variant, th, lds, mix};
     }
     case kDw9: return Plan{kDw9, kWave, 16, kWave};     // no LDS; 16 stands for "fits"
     case kK1Team: return Plan{kK1Team, kWave, 16, kWave};
@@ -244,22 +248,13 @@ int launch_part(const Group& g, size_t begin, size_t end, int qmax, int mode, in
                                                 SQ_K9_ROW_X(SQUANT_W_BF16, 2)};
   static const kernel_t k9x4_one_wave[4] = SQ_K9_ROW_X(SQUANT_W_F32, 1);
 #undef SQ_K9_ROW_X
-#define SQ_K1_ROW(T, NV)                                                                      \
-  {squant_channel_k1<T, SQUANT_MODE_E, NV>, squant_channel_k1<T, SQUANT_MODE_E, NV>,          \
-   squant_channel_k1<T, SQUANT_MODE_EKC, NV>, squant_channel_k1<T, SQUANT_MODE_EKC, NV>}
+#define SQ_K1_ROW(NV)                                                                         \
+  {squant_channel_k1<SQUANT_MODE_E, NV>, squant_channel_k1<SQUANT_MODE_E, NV>,                \
+   squant_channel_k1<SQUANT_MODE_EKC, NV>, squant_channel_k1<SQUANT_MODE_EKC, NV>}
   // (for one-element kernels E&K equals E and E&C equals E&K&C)
-  static const kernel_t k1x1[4] = SQ_K1_ROW(256, 1);
-  static const kernel_t k1x2[4] = SQ_K1_ROW(256, 2);
-  static const kernel_t k1x3[4] = SQ_K1_ROW(256, 3);
-  static const kernel_t k1x4[4] = SQ_K1_ROW(256, 4);
-  static const kernel_t k1x5[4] = SQ_K1_ROW(256, 5);
-  static const kernel_t k1x6[4] = SQ_K1_ROW(256, 6);
-  static const kernel_t k1x7[4] = SQ_K1_ROW(256, 7);
-  static const kernel_t k1x8[4] = SQ_K1_ROW(1024, 8);
-  static const kernel_t k1x8_small[4] = SQ_K1_ROW(256, 8);
-  static const kernel_t k1x8_mid[4] = SQ_K1_ROW(768, 8);
-  static const kernel_t k1x5_mid[4] = SQ_K1_ROW(768, 5);
-  static const kernel_t k1x6_mid[4] = SQ_K1_ROW(768, 6);
+  static const kernel_t k1[8][4] = {SQ_K1_ROW(1), SQ_K1_ROW(2), SQ_K1_ROW(3), SQ_K1_ROW(4),
+                                    SQ_K1_ROW(5), SQ_K1_ROW(6), SQ_K1_ROW(7), SQ_K1_ROW(8)};
+  static const kernel_t k1x16[4] = SQ_K1_ROW(16);
 #undef SQ_K1_ROW
   static const kernel_t k1s[4] = {squant_channel_k1_stream<SQUANT_MODE_E>, squant_channel_k1_stream<SQUANT_MODE_E>,
                                   squant_channel_k1_stream<SQUANT_MODE_EKC>, squant_channel_k1_stream<SQUANT_MODE_EKC>};
@@ -276,14 +271,8 @@ int launch_part(const Group& g, size_t begin, size_t end, int qmax, int mode, in
   const kernel_t kernel = is_ks(g.variant) ? ks_kernel(g.variant, g.threads, mode)
                           : g.variant == kKsMixed ? ksmixed[mode]
                           : (g.variant == kMixed || g.variant == kMixedWave) ? mixed[mode]
-                          : g.variant == kK1x1 ? k1x1[mode]
-                          : g.variant == kK1x2 ? k1x2[mode]
-                          : g.variant == kK1x3 ? k1x3[mode]
-                          : g.variant == kK1x4 ? k1x4[mode]
-                          : g.variant == kK1x5 ? (g.threads <= 256 ? k1x5[mode] : k1x5_mid[mode])
-                          : g.variant == kK1x6 ? (g.threads <= 256 ? k1x6[mode] : k1x6_mid[mode])
-                          : g.variant == kK1x7 ? k1x7[mode]
-                          : g.variant == kK1x8 ? (g.threads <= 256 ? k1x8_small[mode] : g.threads <= 768 ? k1x8_mid[mode] : k1x8[mode])
+                          : g.variant == kK1x16 ? k1x16[mode]
+                          : k1_variant_nv(g.variant) ? k1[k1_variant_nv(g.variant) - 1][mode]
                           : g.variant == kK1Stream ? k1s[mode]
                           : g.variant == kStream ? stream[mode]
                           : g.variant == kDw9 ? dw9[mode]

@@ -18,6 +18,7 @@ enum Variant {
   kK1Team = 10,                                // 1x1 / FC up to kMaxTeamCin: 4 to 16 channels per wave
   kK1x3 = 11, kK1x5 = 12, kK1x6 = 13, kK1x7 = 14,  // 1x1 / FC: 3, 5, 6, 7 vectors per thread
   kStream = 15,                                // any shape: nothing kept on chip, weights walked repeatedly
+  kK1x16 = 16,                                 // 1x1 / FC: 16 vectors per thread
   kKs = 1024                                   // small kernels in registers: kKs + 4 * K + log2(kernels per thread)
 };
 
@@ -27,19 +28,49 @@ constexpr int kMaxTeamCin = 256;  // 1x1 channels this short share a wave
 
 SQ_HD int64_t round_up64(int64_t v) { return (v + 63) / 64 * 64; }
 
-// Workgroup size for a 1x1 / FC channel of more than 1024 vectors in whole multiples of four
-// waves, so that the waves of a workgroup spread evenly over the four SIMDs of a compute unit,
-// and the vectors per thread that go with it.
-SQ_HD int64_t k1_wide_threads(int64_t nvec) {
-  return nvec <= 2048 ? 256 : nvec <= 4096 ? 512 : nvec <= 6144 ? 768 : 1024;
+// Launch shape of the 1x1 / FC kernel for a channel of nvec 16-byte vectors (at most 8192):
+// T threads of NV vectors each, NV in 1..8 or 16.  Candidates: workgroups of one or two waves
+// or a whole multiple of four (which spread evenly over the four SIMDs of a compute unit) with
+// NV = ceil(nvec / T) up to 8, and sixteen vectors in the fewest waves that cover the channel
+// (up to four, else eight).  The score is the share of the T * NV vector slots in use (an idle
+// vector still runs SQuant-E), weighted by what was measured on channels of 512 to 32768
+// elements as a fraction of the HBM roofline: seven or eight vectors (80 VGPRs, six waves per
+// SIMD) 0.85 of one to six or sixteen; 512 threads 0.95, 768 and 1024 threads 0.85 (the
+// workgroup-wide steps of the channel stage run in more waves), sixteen vectors in 512 threads
+// 0.90.  Ties go to the larger NV.  Examples: cin 3072 6 x 128 at 70 %, 4096 16 x 64 at 70 %,
+// 8192 16 x 128 at 67 %, 16384 16 x 256 at 64 %, 24576 6 x 1024 at 55 %, 32768 16 x 512 at
+// 56 % (8 x 1024, one workgroup per compute unit: 33 %); workgroups of 3, 5 to 7 or 9 to 15
+// waves with up to eight vectors lose 10 to 25 points against their neighbours.
+struct K1Shape { int nv; int threads; };
+SQ_HD K1Shape k1_shape(int64_t nvec) {
+  K1Shape best = {8, 1024};
+  int64_t best_score = -1;
+  auto consider = [&](int nv, int64_t T, int64_t weight) {
+    if (nv * T < nvec) return;
+    const int64_t score = nvec * weight * 1000 / (nv * T);
+    if (score > best_score || (score == best_score && nv > best.nv)) {
+      best_score = score;
+      best.nv = nv;
+      best.threads = (int)T;
+    }
+  };
+  const int sizes[6] = {64, 128, 256, 512, 768, 1024};
+  for (int i = 0; i < 6; ++i) {
+    const int64_t T = sizes[i];
+    const int64_t nv = (nvec + T - 1) / T;
+    if (nv > 8) continue;
+    consider((int)nv, T, (nv >= 7 ? 85 : 100) * (T >= 768 ? 85 : T == 512 ? 95 : 100));
+  }
+  const int64_t t16 = round_up64((nvec + 15) / 16);
+  if (t16 <= 256) consider(16, t16, 100 * 100);
+  else if (t16 <= 512) consider(16, 512, 100 * 90);
+  return best;
 }
-SQ_HD int k1_wide_nv(int64_t nvec) {
-  const int64_t T = k1_wide_threads(nvec);
-  return (int)((nvec + T - 1) / T);
-}
+SQ_HD int64_t k1_threads_for(int64_t nvec) { return k1_shape(nvec).threads; }
+SQ_HD int k1_nv_for(int64_t nvec) { return k1_shape(nvec).nv; }
 // Threads a 1x1 / FC channel of nvec vectors takes with nv vectors per thread.
 SQ_HD int64_t k1_threads(int64_t nvec, int nv) {
-  if (nvec > 1024 && nv <= 6 && k1_wide_nv(nvec) == nv) return k1_wide_threads(nvec);
+  if (nv == k1_nv_for(nvec)) return k1_threads_for(nvec);
   return round_up64((nvec + nv - 1) / nv);
 }
 
@@ -48,12 +79,13 @@ SQ_HD int k1_variant_nv(int variant) {
   switch (variant) {
     case kK1x1: return 1; case kK1x2: return 2; case kK1x3: return 3; case kK1x4: return 4;
     case kK1x5: return 5; case kK1x6: return 6; case kK1x7: return 7; case kK1x8: return 8;
+    case kK1x16: return 16;
     default: return 0;
   }
 }
 SQ_HD int k1_variant_of(int nv) {
   const int v[9] = {kGeneric, kK1x1, kK1x2, kK1x3, kK1x4, kK1x5, kK1x6, kK1x7, kK1x8};
-  return v[nv];
+  return nv == 16 ? kK1x16 : v[nv];
 }
 
 // Small kernels held in registers (squant_ks.h): the kernel sizes it is built for, and the
@@ -122,31 +154,7 @@ SQ_HD int choose_variant(int64_t N, int64_t K, bool aligned) {
     return best_c == 4 ? kK9x4 : best_c == 2 ? kK9x2 : kK9x1;
   }
   if (family == 1) {
-    // 16-byte vectors per thread, NV, with T = round_up64(ceil(nvec / NV)) threads: one wave
-    // while that takes at most seven per thread (below); else up to five (five where it fills
-    // the lanes better than four: cin 2560 32 %, cin 3584 17 % faster)
-    // while that needs at most 256 threads, else five to eight (measured: spreading a channel
-    // over more threads sooner is up to 1.6x slower, the workgroup-wide steps of the channel
-    // stage then run in more waves); within the class the count that leaves the fewest
-    // thread-vector slots NV * T idle, the larger one on ties.  Beyond 256 threads only eight.
-    const int64_t nvec = N / 4;
-    // wide channels: five or six vectors per thread in workgroups of 256, 512 or 768 threads
-    // where that covers the channel (measured 11-23 % faster than eight vectors in a workgroup
-    // of 5-7 or 9-11 waves at cin 6144, 9216-12288, 18432; with seven the gain is lost to spills)
-    if (nvec > 1024 && k1_wide_nv(nvec) <= 6) return k1_variant_of(k1_wide_nv(nvec));
-    if (nvec > 2048) return kK1x8;
-    // one wave per channel up to seven vectors per thread (cin 1028..1792: measured 5-37 %
-    // faster than two waves of three or four; eight in one wave is 9 % slower than two of four)
-    if (nvec > 256 && nvec <= 448) return k1_variant_of((int)((nvec + 63) / 64));
-    const int lo = nvec <= 1024 ? 1 : 5, hi = nvec <= 1024 ? 5 : 8;
-    int best = hi;
-    int64_t best_slots = INT64_MAX;
-    for (int nv = hi; nv >= lo; --nv) {
-      const int64_t th = round_up64((nvec + nv - 1) / nv);
-      if (th > 256) continue;
-      if (nv * th < best_slots) { best_slots = nv * th; best = nv; }
-    }
-    return k1_variant_of(best);
+    return k1_variant_of(k1_nv_for(N / 4));
   }
   if (family == 2) return kK1Stream;
   if (family == 3) return kDw9;

@@ -11,6 +11,14 @@ using namespace squant;
 
 int main() {
   long bad = 0, k9 = 0, k1 = 0, stream = 0, team = 0, small = 0, generic = 0;
+  // 1x1 / FC launch shapes: the measured optima
+  const struct { int64_t cin; int nv, threads; } optima[] = {
+      {512, 2, 64},     {1024, 4, 64},    {3072, 6, 128},    {4096, 16, 64},   {5120, 5, 256},   {8192, 16, 128},
+      {12288, 16, 192}, {16384, 16, 256}, {24576, 6, 1024}, {28672, 16, 512}, {32768, 16, 512}};
+  for (const auto& o : optima) {
+    const K1Shape sh = k1_shape(o.cin / 4);
+    bad += sh.nv != o.nv || sh.threads != o.threads;
+  }
   for (int aligned = 0; aligned < 2; ++aligned)
     for (int64_t K : {1, 2, 3, 4, 5, 6, 7, 8, 9, 25, 49})
       for (int64_t N = 1; N <= 40000; N += (N < 600 ? 1 : 61)) {
@@ -42,24 +50,15 @@ int main() {
           if (nv == 0 || K != 1 || !aligned || N % 4 || N > kMaxK1Cin || N <= kMaxTeamCin) { ++bad; continue; }
           const int64_t nvec = N / 4, threads = k1_threads(nvec, nv);
           bad += threads * nv < nvec;
-          bad += threads % 64 != 0 || threads > (nv == 8 ? 1024 : nv >= 5 && nv <= 6 ? 768 : 256);
           bad += k1_variant_of(nv) != v;
-          if (nvec > 1024 && k1_wide_nv(nvec) <= 6) {
-            // wide channels: five or six vectors per thread in 256, 512 or 768 threads
-            bad += nv != k1_wide_nv(nvec) || nv < 5 || threads != k1_wide_threads(nvec) || threads % 256 != 0;
-            continue;
-          }
-          // up to five vectors per thread while 256 threads suffice for that, else five to eight;
-          // no admissible count of the class leaves fewer thread-vector slots idle
-          if (nvec > 256 && nvec <= 448) {  // one wave of five to seven vectors per thread
-            bad += nv != (nvec + 63) / 64 || threads != 64;
-            continue;
-          }
-          bad += nvec <= 1024 ? nv > 5 : nv < 5;
-          for (int c = (nvec <= 1024 ? 1 : 5); c <= (nvec <= 1024 ? 5 : 8) && nvec <= 2048; ++c) {
-            const int64_t th = round_up64((nvec + c - 1) / c);
-            if (th > 256) continue;
-            bad += c * th < nv * threads;
+          // eight or fewer vectors in one or two waves or a multiple of four, or sixteen vectors
+          // in any whole waves up to four, or eight
+          bad += !((nv >= 1 && nv <= 8) || nv == 16);
+          if (nv <= 8) {
+            bad += !(threads == 64 || threads == 128 || (threads % 256 == 0 && threads <= 1024));
+            bad += nv != (nvec + threads - 1) / threads;  // no thread without a vector of its own
+          } else {
+            bad += threads % 64 != 0 || (threads > 256 && threads != 512);
           }
         } else if (family == 3) {
           bad += v != kDw9 || K != 9 || N != 1;

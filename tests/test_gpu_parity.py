@@ -72,7 +72,7 @@ SHAPES = [
     (10, 1, 1, 1), (17, 63, 1, 1), (1000, 512, 1, 1), (12, 2048, 1, 1), (3, 5000, 1, 1),
     (9, 100, 2, 2), (6, 37, 1, 3), (5, 50, 4, 4), (2, 3000, 3, 3),
     (7, 100, 1, 1), (7, 1028, 1, 1), (5, 4096, 1, 1), (3, 8192, 1, 1), (2, 32768, 1, 1),
-    (2, 32764, 1, 1), (40, 16, 1, 1), (6, 128, 3, 3), (6, 96, 3, 3), (6, 192, 3, 3), (3, 4096, 3, 3),
+    (2, 32764, 1, 1), (2, 26000, 1, 1), (3, 20000, 1, 1), (40, 16, 1, 1), (6, 128, 3, 3), (6, 96, 3, 3), (6, 192, 3, 3), (3, 4096, 3, 3),
 ]
 
 
