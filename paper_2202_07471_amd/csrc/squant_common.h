@@ -37,6 +37,7 @@ struct LaunchArgs {
   int32_t mode;
   int32_t out_format;       // squant_output_t
   int32_t wtype;            // squant_wtype_t
+  int32_t wave_span;        // channels a wave of the wave-per-channel 1x1 routine walks
   TensorDesc table[kInlineDescs];
 };
 

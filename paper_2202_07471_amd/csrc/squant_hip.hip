@@ -25,6 +25,7 @@
 #include "squant_k9.h"
 #include "squant_ks.h"
 #include "squant_k1.h"
+#include "squant_k1_wave.h"
 #include "squant_mixed.h"
 #include "squant_stream.h"
 #include "squant_act.h"
@@ -99,6 +100,7 @@ struct Group {
   size_t lds;
   std::vector<TensorDesc> t;
   bool fixed_threads = false;  // mixed launch: a non-generic member has set the workgroup size
+  bool wave_members = false;   // holds wave-per-channel 1x1 tensors: LDS for a selection area per wave
 };
 
 // threads / lds: of a launch of the tensor's own variant.  mix_threads: what the tensor needs as
@@ -117,6 +119,8 @@ Plan stream_plan(int64_t N) {
 // Picks the kernel variant and launch shape for one tensor (every tensor fits one).
 Plan plan_tensor(const void* w, const void* out, int64_t N, int64_t K, int lds_limit) {
   const int variant = choose_variant(N, K, pointers_aligned(w, out));
+  // LDS: a selection area per wave of the launch's workgroup, added when the launch goes out
+  if (is_k1_wave(variant)) return Plan{variant, kK1WaveThreads, 16, kWave};
   switch (variant) {
     case kK9x1: case kK9x2: case kK9x4: {
       const int kpt = variant == kK9x4 ? 4 : variant == kK9x2 ? 2 : 1;
@@ -202,12 +206,13 @@ kernel_t ks_kernel(int variant, int threads, int mode) {
 
 // Launches tensors [begin, end) of a group (at most kInlineDescs of them) as one kernel.
 int launch_part(const Group& g, size_t begin, size_t end, int qmax, int mode, int output, int wtype,
-                hipStream_t st) {
+                int wave_span, hipStream_t st) {
   LaunchArgs a{};
   int64_t total = 0;
   bool uniform = true;
   auto items_of = [&](const TensorDesc& t) {
-    return work_items(t.M, t.N, t.K, g.threads, choose_family(t.N, t.K, pointers_aligned(t.w, t.out)));
+    return work_items(t.M, t.N, t.K, g.threads, choose_family(t.N, t.K, pointers_aligned(t.w, t.out)),
+                      wave_span);
   };
   const int64_t items0 = items_of(g.t[begin]);
   for (size_t i = begin; i < end; ++i) {
@@ -231,6 +236,7 @@ int launch_part(const Group& g, size_t begin, size_t end, int qmax, int mode, in
   a.mode = mode;
   a.out_format = output;
   a.wtype = wtype;
+  a.wave_span = wave_span;
 #define SQ_K9_ROW(T, KPT)                                                                     \
   {squant_channel_k9<T, SQUANT_MODE_E, KPT>, squant_channel_k9<T, SQUANT_MODE_EK, KPT>,       \
    squant_channel_k9<T, SQUANT_MODE_EKC, KPT>, squant_channel_k9<T, SQUANT_MODE_EC, KPT>}
@@ -255,6 +261,12 @@ int launch_part(const Group& g, size_t begin, size_t end, int qmax, int mode, in
   static const kernel_t k1[8][4] = {SQ_K1_ROW(1), SQ_K1_ROW(2), SQ_K1_ROW(3), SQ_K1_ROW(4),
                                     SQ_K1_ROW(5), SQ_K1_ROW(6), SQ_K1_ROW(7), SQ_K1_ROW(8)};
   static const kernel_t k1x16[4] = SQ_K1_ROW(16);
+#define SQ_K1W_ROW(NV)                                                                        \
+  {squant_channel_k1_wave<SQUANT_MODE_E, NV>, squant_channel_k1_wave<SQUANT_MODE_E, NV>,      \
+   squant_channel_k1_wave<SQUANT_MODE_EKC, NV>, squant_channel_k1_wave<SQUANT_MODE_EKC, NV>}
+  static const kernel_t k1w[7][4] = {SQ_K1W_ROW(2), SQ_K1W_ROW(3), SQ_K1W_ROW(4), SQ_K1W_ROW(5),
+                                     SQ_K1W_ROW(6), SQ_K1W_ROW(7), SQ_K1W_ROW(8)};
+#undef SQ_K1W_ROW
 #undef SQ_K1_ROW
   static const kernel_t k1s[4] = {squant_channel_k1_stream<SQUANT_MODE_E>, squant_channel_k1_stream<SQUANT_MODE_E>,
                                   squant_channel_k1_stream<SQUANT_MODE_EKC>, squant_channel_k1_stream<SQUANT_MODE_EKC>};
@@ -272,6 +284,7 @@ int launch_part(const Group& g, size_t begin, size_t end, int qmax, int mode, in
                           : g.variant == kKsMixed ? ksmixed[mode]
                           : (g.variant == kMixed || g.variant == kMixedWave) ? mixed[mode]
                           : g.variant == kK1x16 ? k1x16[mode]
+                          : is_k1_wave(g.variant) ? k1w[g.variant - kK1Wave - 2][mode]
                           : k1_variant_nv(g.variant) ? k1[k1_variant_nv(g.variant) - 1][mode]
                           : g.variant == kK1Stream ? k1s[mode]
                           : g.variant == kStream ? stream[mode]
@@ -284,24 +297,34 @@ int launch_part(const Group& g, size_t begin, size_t end, int qmax, int mode, in
                                                   : g.threads <= 256 ? k9x4[mode] : k9x4_large[mode])
                                                : squant_channel_generic;
   if (!kernel) return SQUANT_ERR_UNSUPPORTED;
-  if (g.lds > 48 * 1024) {
+  size_t lds = g.lds;
+  if (g.wave_members) lds = std::max(lds, (size_t)(g.threads / kWave) * sizeof(K1WaveSel));
+  if (lds > 48 * 1024) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)g.lds) != hipSuccess) {
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
       (void)hipGetLastError();
       return SQUANT_ERR_DEVICE;
     }
   }
   const unsigned grid = (unsigned)total;
-  hipLaunchKernelGGL(kernel, dim3(grid), dim3(g.threads), g.variant == kStream ? 0 : g.lds, st, a);
+  hipLaunchKernelGGL(kernel, dim3(grid), dim3(g.threads), g.variant == kStream ? 0 : lds, st, a);
   if (hipGetLastError() != hipSuccess) return SQUANT_ERR_DEVICE;
   return SQUANT_OK;
 }
 
 // A group goes out in launches of at most kInlineDescs tensors each.
 int launch_group(const Group& g, int qmax, int mode, int output, int wtype, hipStream_t st) {
+  // Waves of the wave-per-channel 1x1 kernel walk several channels each where that still
+  // leaves the chip (8192 resident waves) a few rounds of them; in a mixed launch one.
+  int wave_span = 1;
+  if (is_k1_wave(g.variant)) {
+    int64_t channels = 0;
+    for (const auto& t : g.t) channels += t.M;
+    if (channels >= (int64_t)kK1WaveSpan * 2 * 8192) wave_span = kK1WaveSpan;
+  }
   for (size_t begin = 0; begin < g.t.size(); begin += kInlineDescs) {
     const size_t end = std::min(g.t.size(), begin + (size_t)kInlineDescs);
-    if (int rc = launch_part(g, begin, end, qmax, mode, output, wtype, st)) return rc;
+    if (int rc = launch_part(g, begin, end, qmax, mode, output, wtype, wave_span, st)) return rc;
   }
   return SQUANT_OK;
 }
@@ -324,6 +347,7 @@ int squant_quantize_ex(const void* d_w, squant_wtype_t wtype, int32_t cout, int3
   if (p.lds == 0) return SQUANT_ERR_UNSUPPORTED;
   Group g{p.variant, p.threads, p.lds, {}};
   g.t.push_back(TensorDesc{d_w, d_out, d_scales, cout, cin, (int32_t)K, 0});
+  g.wave_members = is_k1_wave(p.variant);
   return launch_group(g, (1 << (bits - 1)) - 1, (int)mode, (int)output, (int)wtype,
                       (hipStream_t)stream);
 }
@@ -450,6 +474,7 @@ int squant_quantize_batched_ex(const squant_tensor_t* h_tensors, int32_t n_tenso
       g->lds = std::max(g->lds, p.lds);
     }
     g->t.push_back(TensorDesc{t.w, t.codes, t.scales, t.cout, t.cin, (int32_t)((int64_t)t.kh * t.kw), 0});
+    g->wave_members |= is_k1_wave(p.variant);
   }
   hipStream_t st = (hipStream_t)stream;
   const int qmax = (1 << (bits - 1)) - 1;

@@ -47,12 +47,41 @@ __device__ __forceinline__ vf4 load_global_f4_stream(const float* p) {
 // shares bin 128 with small positive P: when the scan ends in that bin the members are
 // counted again exactly.
 // ---------------------------------------------------------------------------
+// The routines below serve a whole workgroup on one channel (WAVE = false) or a single wave on
+// a channel of its own (WAVE = true, squant_k1_wave.h): then the "threads" are the wave's lanes
+// and a barrier only has to keep the compiler from moving LDS accesses across it (the LDS
+// handles a wave's instructions in order).  `Sel` is SelectShared or a structure with the same
+// members.
+template <bool WAVE>
+__device__ __forceinline__ int k1_tid() {
+  if (!WAVE) return (int)threadIdx.x;
+  // The wave kernel calls from inside its loop over channels.  The empty statement keeps the
+  // compiler from computing everything that depends on the lane once before that loop, where
+  // it does not fit the registers and comes back from scratch memory in every round.
+  int lane = (int)(threadIdx.x & (kWave - 1));
+  asm volatile("" : "+v"(lane));
+  return lane;
+}
+template <bool WAVE>
+__device__ __forceinline__ int k1_team() { return WAVE ? kWave : (int)blockDim.x; }
+template <bool WAVE>
+__device__ __forceinline__ void k1_sync() {
+  if (WAVE) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  } else {
+    __syncthreads();
+  }
+}
+
 __device__ __forceinline__ void k1_count(SelectShared& sh, int32_t P) {
   atomicAdd(&sh.hist[(P >> 15) + 128], 1u);
 }
 // The same for a perturbation in biased form: bits 15..23 of kQ23Bias + P are 128 + (P >> 15)
 // (the bias has 128 there and zeros below, and the bin stays within 0..256).
-__device__ __forceinline__ void k1_count_biased(SelectShared& sh, uint32_t pb) {
+template <typename Sel>
+__device__ __forceinline__ void k1_count_biased(Sel& sh, uint32_t pb) {
   static_assert(((kQ23Bias >> 15) & 511u) == 128u && (kQ23Bias & 0x7FFFu) == 0u, "bin taken from the biased bits");
   atomicAdd(&sh.hist[(pb >> 15) & 511u], 1u);
 }
@@ -127,13 +156,14 @@ constexpr int kK1MaxThreads = 1024;  // the owner word has ten bits for the thre
 __device__ __forceinline__ uint32_t k1_owner_word(int tid, int q) {
   return ((uint32_t)(q >> 2) << 12) | ((uint32_t)tid << 2) | (uint32_t)(q & 3);
 }
-template <typename MaskT>
-__device__ __forceinline__ MaskT k1_rank_list_owner(SelectShared& sh, uint32_t* owner_mask, uint32_t count,
+template <typename MaskT, bool WAVE = false, typename Sel>
+__device__ __forceinline__ MaskT k1_rank_list_owner(Sel& sh, uint32_t* owner_mask, uint32_t count,
                                                     uint32_t need) {
-  const uint32_t sub = threadIdx.x & 3u, groups = (count + 3u) >> 2;
+  const uint32_t tid = (uint32_t)k1_tid<WAVE>(), T = (uint32_t)k1_team<WAVE>();
+  const uint32_t sub = tid & 3u, groups = (count + 3u) >> 2;
   const uint4* key4 = reinterpret_cast<const uint4*>(sh.list_key);
   const uint4* n4 = reinterpret_cast<const uint4*>(sh.list_n);
-  for (uint32_t i = threadIdx.x >> 2; i < count; i += blockDim.x >> 2) {
+  for (uint32_t i = tid >> 2; i < count; i += T >> 2) {
     const uint32_t key = sh.list_key[i], n = sh.list_n[i];
     int rank = 0;
     for (uint32_t g = sub; g < groups; g += 4) {
@@ -147,24 +177,26 @@ __device__ __forceinline__ MaskT k1_rank_list_owner(SelectShared& sh, uint32_t* 
     rank += __builtin_amdgcn_update_dpp(0, rank, 0x4E, 0xf, 0xf, true);  // quad_perm [2,3,0,1]
     if (sub == 0 && (uint32_t)rank < need) {
       const uint32_t j = n >> 12, t = (n >> 2) & (uint32_t)(kK1MaxThreads - 1);
-      atomicOr(&owner_mask[(j >> 3) * blockDim.x + t], 1u << (4u * (j & 7u) + (n & 3u)));
+      atomicOr(&owner_mask[(j >> 3) * T + t], 1u << (4u * (j & 7u) + (n & 3u)));
     }
   }
-  __syncthreads();
-  MaskT mine = owner_mask[threadIdx.x];
-  if (sizeof(MaskT) > 4) mine |= (MaskT)owner_mask[blockDim.x + threadIdx.x] << (8 * sizeof(MaskT) - 32);
+  k1_sync<WAVE>();
+  MaskT mine = owner_mask[tid];
+  if (sizeof(MaskT) > 4) mine |= (MaskT)owner_mask[T + tid] << (8 * sizeof(MaskT) - 32);
   return mine;
 }
 
 // Empties the ranking list (see k1_rank_list); with select_reset, before the first barrier.
-__device__ __forceinline__ void k1_list_reset(SelectShared& sh) {
-  for (int b = threadIdx.x; b < kListCap / 4; b += blockDim.x) {
+template <bool WAVE = false, typename Sel>
+__device__ __forceinline__ void k1_list_reset(Sel& sh) {
+  for (int b = k1_tid<WAVE>(); b < kListCap / 4; b += k1_team<WAVE>()) {
     reinterpret_cast<uint4*>(sh.list_key)[b] = make_uint4(0, 0, 0, 0);
     reinterpret_cast<uint4*>(sh.list_n)[b] = make_uint4(~0u, ~0u, ~0u, ~0u);
   }
 }
 
-__device__ __forceinline__ void k1_push(SelectShared& sh, uint32_t key, int n) {
+template <typename Sel>
+__device__ __forceinline__ void k1_push(Sel& sh, uint32_t key, int n) {
   const uint32_t slot = atomicAdd(&sh.list_count, 1u);
   sh.list_key[slot] = key;
   sh.list_n[slot] = (uint32_t)n;
@@ -176,11 +208,11 @@ __device__ __forceinline__ void k1_push(SelectShared& sh, uint32_t key, int n) {
 // (bit q).  The common case costs four instructions an element: with u = P (sum > 0) or ~P
 // (sum < 0), u >= thr is P >= thr resp. P <= ~thr, a compare on the biased value whose result
 // is shifted into a mask.
-template <int NE, typename MaskT>
+template <int NE, typename MaskT, bool WAVE = false, typename Sel>
 __device__ __forceinline__ MaskT k1_channel_stage(const uint32_t (&B)[NE], int sgn, uint32_t need,
-                                                  SelectShared& sh, uint32_t* owner_mask) {
+                                                  Sel& sh, uint32_t* owner_mask) {
   static_assert(NE <= 8 * (int)sizeof(MaskT), "one mask bit per element");
-  const int T = blockDim.x, tid = threadIdx.x;
+  const int T = k1_team<WAVE>(), tid = k1_tid<WAVE>();
   const int32_t smask = sgn < 0 ? -1 : 0;
   auto bit = [](int q) { return (MaskT)1 << q; };
   // mask of the elements with u >= thr: a compare into the carry and an add-with-carry that
@@ -243,9 +275,9 @@ __device__ __forceinline__ MaskT k1_channel_stage(const uint32_t (&B)[NE], int s
           if (u > 0 || sm != 0) k1_push(sh, (uint32_t)u, k1_owner_word(tid, q));  // P = 0 is no candidate
         }
     }
-    __syncthreads();
+    k1_sync<WAVE>();
     count = sh.list_count;  // exact: without the P = 0 elements that bin 128 also counts
-    return flip | k1_rank_list_owner<MaskT>(sh, owner_mask, count, need < count ? need : count);
+    return flip | k1_rank_list_owner<MaskT, WAVE>(sh, owner_mask, count, need < count ? need : count);
   }
 
   // ---- a crowded bin: histogram passes over bits 14..7, then 7..0 of u ----
@@ -254,11 +286,11 @@ __device__ __forceinline__ MaskT k1_channel_stage(const uint32_t (&B)[NE], int s
 #pragma unroll
     for (int q = 0; q < NE; ++q)
       if (B[q] == kQ23Bias) live &= ~bit(q);
-    __syncthreads();
+    k1_sync<WAVE>();
     if (tid == 0) sh.wave_cnt[16] = 0;
-    __syncthreads();
+    k1_sync<WAVE>();
     if (live) atomicAdd(&sh.wave_cnt[16], (uint32_t)__popcll((unsigned long long)live));
-    __syncthreads();
+    k1_sync<WAVE>();
     count = sh.wave_cnt[16];
     if (count < need) need = count;
     if (count == 0) return flip;
@@ -266,14 +298,14 @@ __device__ __forceinline__ MaskT k1_channel_stage(const uint32_t (&B)[NE], int s
   int shift = 15;
   while (count > (uint32_t)kListCap && count != need && shift > 0) {
     shift = shift == 15 ? 7 : 0;
-    __syncthreads();  // every wave has finished reading the histogram
+    k1_sync<WAVE>();  // every wave has finished reading the histogram
     for (int b = tid; b < 256; b += T) sh.hist[b] = 0;
-    __syncthreads();
+    k1_sync<WAVE>();
     sm = opaque(smask);
 #pragma unroll
     for (int q = 0; q < NE; ++q)
       if (live & bit(q)) atomicAdd(&sh.hist[((uint32_t)u_of(q, sm) >> shift) & 255u], 1u);
-    __syncthreads();
+    k1_sync<WAVE>();
     const uint32_t d2 = scan_histogram_top(sh.hist, need, need_at, count);
     need = need_at;
     sm = opaque(smask);
@@ -293,8 +325,8 @@ __device__ __forceinline__ MaskT k1_channel_stage(const uint32_t (&B)[NE], int s
 #pragma unroll
     for (int q = 0; q < NE; ++q)
       if (live & bit(q)) k1_push(sh, (uint32_t)u_of(q, sm), k1_owner_word(tid, q));
-    __syncthreads();
-    return flip | k1_rank_list_owner<MaskT>(sh, owner_mask, count, need);
+    k1_sync<WAVE>();
+    return flip | k1_rank_list_owner<MaskT, WAVE>(sh, owner_mask, count, need);
   }
   // more than kListCap elements equal in all their bits: the lowest indices flip.  The four
   // elements of a vector are consecutive and vectors ascend with the thread, so inside round
@@ -307,9 +339,9 @@ __device__ __forceinline__ MaskT k1_channel_stage(const uint32_t (&B)[NE], int s
     const uint32_t bits = (uint32_t)(live >> (4 * round)) & 15u;
     const uint32_t mine = (uint32_t)__popc(bits);
     const uint32_t incl = wave_prefix_sum(mine);
-    __syncthreads();
+    k1_sync<WAVE>();
     if (lane == kWave - 1) sh.wave_cnt[wid] = incl;
-    __syncthreads();
+    k1_sync<WAVE>();
     uint32_t base = done + incl - mine, total = 0;
     for (int w = 0; w < nw; ++w) {
       const uint32_t c = sh.wave_cnt[w];

@@ -8,6 +8,7 @@
 #include "squant_generic.h"
 #include "squant_k1.h"
 #include "squant_k1_team.h"
+#include "squant_k1_wave.h"
 #include "squant_k9.h"
 #include "squant_plan.h"
 
@@ -48,6 +49,8 @@ __global__ void __launch_bounds__(kMixedMaxThreads)
     dw9_channels<MODE>(a, d, m);
   } else if (family == 4) {
     k1_team_dispatch<M1>(a, d, m);
+  } else if (family == 6) {
+    k1_wave_dispatch<M1>(a, d, m, smem);
   } else {
     generic_channel(a, d, m, smem, gs);
   }

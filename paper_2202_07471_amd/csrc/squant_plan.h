@@ -19,12 +19,16 @@ enum Variant {
   kK1x3 = 11, kK1x5 = 12, kK1x6 = 13, kK1x7 = 14,  // 1x1 / FC: 3, 5, 6, 7 vectors per thread
   kStream = 15,                                // any shape: nothing kept on chip, weights walked repeatedly
   kK1x16 = 16,                                 // 1x1 / FC: 16 vectors per thread
+  kK1Wave = 32,                                // 1x1 / FC up to kMaxWaveCin, a wave per channel: kK1Wave + vectors per lane (2..8)
   kKs = 1024                                   // small kernels in registers: kKs + 4 * K + log2(kernels per thread)
 };
 
 constexpr int kMaxK9Cin = 4096;   // 3x3 variant: cin % 4 == 0 up to here
 constexpr int kMaxK1Cin = 32768;  // 1x1 variant: cin % 4 == 0 up to here
 constexpr int kMaxTeamCin = 256;  // 1x1 channels this short share a wave
+constexpr int kMaxWaveCin = 2048; // 1x1 channels up to here take a wave each (at most 8 vectors per lane)
+constexpr int kK1WaveSpan = 4;    // consecutive channels a wave of that kernel walks in a large launch (1 in others)
+constexpr int kK1WaveThreads = 256;  // its workgroup in a launch of its own
 
 SQ_HD int64_t round_up64(int64_t v) { return (v + 63) / 64 * 64; }
 
@@ -74,6 +78,10 @@ SQ_HD int64_t k1_threads(int64_t nvec, int nv) {
   return round_up64((nvec + nv - 1) / nv);
 }
 
+// The wave-per-channel 1x1 / FC kernel: 16-byte vectors per lane of a channel of N elements.
+SQ_HD int k1_wave_nv(int64_t N) { return (int)((N / 4 + 63) / 64); }
+SQ_HD bool is_k1_wave(int variant) { return variant >= kK1Wave + 2 && variant <= kK1Wave + 8; }
+
 // 16-byte vectors per thread of a 1x1 / FC variant (0: not one), and back.
 SQ_HD int k1_variant_nv(int variant) {
   switch (variant) {
@@ -122,12 +130,13 @@ SQ_HD int ks_variant_kpt(int variant) { return 1 << ((variant - kKs) & 3); }
 
 // Kernel family of a tensor: 9 = the 3x3 kernel, 1 = the 1x1 / FC kernel, 2 = the streaming
 // 1x1 / FC kernel, 3 = depthwise 3x3, 4 = short 1x1 / FC channels (several per wave), 5 = other
-// small kernels in registers, 0 = generic.
+// small kernels in registers, 6 = 1x1 / FC channels that take a wave each, 0 = generic.
 // aligned: weights on 16 bytes and output on 4 (what the vector loads / stores need)
 SQ_HD int choose_family(int64_t N, int64_t K, bool aligned) {
   if (K == 9 && N == 1) return 3;  // any alignment: element-wise loads and stores
   if (K == 9 && (N & 3) == 0 && N <= kMaxK9Cin && aligned) return 9;
   if (K == 1 && (N & 3) == 0 && N <= kMaxTeamCin && aligned) return 4;
+  if (K == 1 && (N & 3) == 0 && N <= kMaxWaveCin && aligned) return 6;
   if (K == 1 && (N & 3) == 0 && N <= kMaxK1Cin && aligned) return 1;
   if (K == 1 && (N & 3) == 0 && aligned) return 2;
   if (N > 1 && aligned && ks_kpt_log2(N, K) >= 0) return 5;
@@ -159,6 +168,7 @@ SQ_HD int choose_variant(int64_t N, int64_t K, bool aligned) {
   if (family == 2) return kK1Stream;
   if (family == 3) return kDw9;
   if (family == 4) return kK1Team;
+  if (family == 6) return kK1Wave + k1_wave_nv(N);
   if (family == 5) return ks_variant(K, ks_kpt_log2(N, K));
   return kGeneric;
 }
@@ -167,11 +177,12 @@ SQ_HD int choose_variant(int64_t N, int64_t K, bool aligned) {
 SQ_HD int team_lanes(int64_t N) { return N <= 16 ? 4 : N <= 32 ? 8 : 16; }
 
 // Workgroups a tensor of M output channels takes in a launch of T threads per workgroup:
-// one per channel, except depthwise 3x3 (every thread has a channel of its own) and short
-// 1x1 channels (one per team of lanes).  `family` as from choose_family.
-SQ_HD int64_t work_items(int64_t M, int64_t N, int64_t K, int64_t T, int family) {
+// one per channel, except depthwise 3x3 (every thread has a channel of its own), short 1x1
+// channels (one per team of lanes) and 1x1 channels of a wave each (wave_span per wave).  `family` as from choose_family.
+SQ_HD int64_t work_items(int64_t M, int64_t N, int64_t K, int64_t T, int family, int wave_span) {
   if (family == 3) return (M + T - 1) / T;
   if (family == 4) { const int64_t per = T / team_lanes(N); return (M + per - 1) / per; }
+  if (family == 6) { const int64_t per = T / 64 * wave_span; return (M + per - 1) / per; }
   (void)K;
   return M;
 }

@@ -10,7 +10,7 @@
 using namespace squant;
 
 int main() {
-  long bad = 0, k9 = 0, k1 = 0, stream = 0, team = 0, small = 0, generic = 0;
+  long bad = 0, k9 = 0, k1 = 0, stream = 0, team = 0, wave = 0, small = 0, generic = 0;
   // 1x1 / FC launch shapes: the measured optima
   const struct { int64_t cin; int nv, threads; } optima[] = {
       {512, 2, 64},     {1024, 4, 64},    {3072, 6, 128},    {4096, 16, 64},   {5120, 5, 256},   {8192, 16, 128},
@@ -47,7 +47,7 @@ int main() {
         } else if (family == 1) {
           ++k1;
           const int nv = k1_variant_nv(v);
-          if (nv == 0 || K != 1 || !aligned || N % 4 || N > kMaxK1Cin || N <= kMaxTeamCin) { ++bad; continue; }
+          if (nv == 0 || K != 1 || !aligned || N % 4 || N > kMaxK1Cin || N <= kMaxWaveCin) { ++bad; continue; }
           const int64_t nvec = N / 4, threads = k1_threads(nvec, nv);
           bad += threads * nv < nvec;
           bad += k1_variant_of(nv) != v;
@@ -60,16 +60,23 @@ int main() {
           } else {
             bad += threads % 64 != 0 || (threads > 256 && threads != 512);
           }
+        } else if (family == 6) {
+          ++wave;  // 1x1 channels that take a wave each
+          bad += !is_k1_wave(v) || K != 1 || !aligned || N % 4 || N <= kMaxTeamCin || N > kMaxWaveCin;
+          const int nv = v - kK1Wave;
+          bad += nv != k1_wave_nv(N) || nv < 2 || nv > 8 || 64 * nv * 4 < N;
+          bad += work_items(130, N, K, 256, family, kK1WaveSpan) != (130 + 4 * kK1WaveSpan - 1) / (4 * kK1WaveSpan);
+          bad += work_items(130, N, K, 64, family, 1) != 130;
         } else if (family == 3) {
           bad += v != kDw9 || K != 9 || N != 1;
-          bad += work_items(130, N, K, 64, family) != 3 || work_items(128, N, K, 64, family) != 2;
+          bad += work_items(130, N, K, 64, family, 1) != 3 || work_items(128, N, K, 64, family, 1) != 2;
         } else if (family == 4) {
           ++team;  // short 1x1 channels: several per wave
           bad += v != kK1Team || K != 1 || !aligned || N % 4 || N > kMaxTeamCin;
           const int lanes = team_lanes(N);
           bad += (lanes != 4 && lanes != 8 && lanes != 16) || 64 % lanes != 0;
           bad += N > 4 * lanes * (lanes == 16 ? 4 : 1);           // vectors per lane: 1, or up to 4 at 16 lanes
-          bad += work_items(130, N, K, 64, family) != (130 + 64 / lanes - 1) / (64 / lanes);
+          bad += work_items(130, N, K, 64, family, 1) != (130 + 64 / lanes - 1) / (64 / lanes);
         } else if (family == 2) {
           ++stream;  // a 1x1 channel too long for the register-resident kernel
           bad += v != kK1Stream || K != 1 || !aligned || N % 4 || N <= kMaxK1Cin;
@@ -103,17 +110,17 @@ int main() {
               bad += (N / c) * threads > (N / kpt) * th;
             }
           }
-          bad += work_items(130, N, K, threads, family) != 130;
+          bad += work_items(130, N, K, threads, family, 1) != 130;
         } else {
           ++generic;
-          bad += v != kGeneric || work_items(130, N, K, 64, family) != 130;
+          bad += v != kGeneric || work_items(130, N, K, 64, family, 1) != 130;
           bad += aligned && K == 9 && N % 4 == 0 && N <= kMaxK9Cin;
           bad += aligned && K == 1 && N % 4 == 0;
           bad += aligned && ks_has(K) && N > 1 && (N * K) % 4 == 0 && N <= 256;  // one kernel per thread always fits
         }
       }
-  std::printf("plan_mismatches=%ld k9=%ld k1=%ld stream=%ld team=%ld small=%ld generic=%ld\n", bad, k9, k1, stream,
-              team, small, generic);
-  bad += small == 0;
+  std::printf("plan_mismatches=%ld k9=%ld k1=%ld stream=%ld team=%ld wave=%ld small=%ld generic=%ld\n", bad, k9, k1,
+              stream, team, wave, small, generic);
+  bad += small == 0 || wave == 0;
   return bad != 0;
 }
