@@ -383,3 +383,26 @@ def test_many_output_channels(sq):
         w = rand_weights(shape, 61, "normal")
         codes, scales = run_single(sq, w, 4, 2)
         assert_same(codes, scales, w, 4, 2, threads=16, what=f"{shape}")
+
+
+def test_wave_kernel_walks_several_channels(sq):
+    """1x1 / FC channels that take a wave each, in launches of more than 65536 channels: there a
+    wave walks four consecutive channels and requests the next one's weights early.  A single
+    tensor with a ragged channel count, and a batch of tensors of another width (seven vectors
+    per lane, the last one ragged) in all three value distributions."""
+    w = rand_weights((70001, 512, 1, 1), 71, "normal")
+    codes, scales = run_single(sq, w, 4, 2)
+    assert_same(codes, scales, w, 4, 2, threads=16, what="70001 x 512")
+    del w, codes, scales
+    kinds = ("normal", "heavy", "grid")
+    ws = [rand_weights((3001, 1540, 1, 1), 500 + i, kinds[i % 3]) for i in range(24)]
+    for bits, mode in ((4, 2), (8, 0)):
+        codes, scales = run_batched(sq, ws, bits, mode)
+        for i in (0, 1, 2, 13, 23):
+            assert_same(codes[i], scales[i], ws[i], bits, mode, threads=16, what=f"tensor {i} of 24 x [3001,1540] {kinds[i % 3]}")
+        rng = np.random.default_rng(3)
+        for i in range(24):
+            for c in rng.integers(0, 3001, 4):
+                want_c, want_s = oracle.quantize(ws[i][c][None], bits, mode)
+                assert np.array_equal(codes[i][c].cpu().numpy().reshape(-1), want_c.reshape(-1)), f"tensor {i} channel {c}"
+                assert scales[i][c].cpu().numpy().view(np.uint32) == want_s.view(np.uint32)[0]
