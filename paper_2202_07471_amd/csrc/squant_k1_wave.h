@@ -91,8 +91,9 @@ __device__ __forceinline__ void k1_wave_channels(const LaunchArgs& a, const Tens
       const float f1 = !prescale ? 1.0f : amax < 1.0f ? 0x1p64f : 0x1p-64f;
       const float a1 = amax * f1;
       const float f2 = !prescale ? 1.0f : a1 < 0x1p-60f ? 0x1p64f : a1 > 0x1p60f ? 0x1p-64f : 1.0f;
-      const float s2 = s * f1 * f2;
-      k1_round_all<NV, kChannelStage>(w, s2, 1.0f / s2, qmaxf, prescale, f1, f2, code, B, esum);
+      const float s2 = s * f1 * f2, rs2 = 1.0f / s2;
+      const bool clamp = prescale || !(div_by_reciprocal(amax * f1 * f2, s2, rs2) <= qmaxf);
+      k1_round_all<NV, kChannelStage>(w, s2, rs2, qmaxf, prescale, clamp, f1, f2, code, B, esum);
     }
     // the weights are used up: the next channel's travel while this one's flips are chosen
     if (PREFETCH && m + 1 < c1) load_channel(m + 1, lane);
