@@ -368,12 +368,10 @@ __device__ __forceinline__ MaskT k1_channel_stage(const uint32_t (&B)[NE], int s
 // SQuant-E for the NV vectors of a thread: the packed biased codes (code + 128, four to a
 // dword) and, WITH_P, the Q23 perturbations in biased form (kQ23Bias + P).  One body for every
 // channel, so that the values have one home in the registers: `prescale` (uniform over the
-// workgroup, almost never set) multiplies the weights by f1 * f2 first, `clamp` (uniform,
-// seldom set) clamps the quotients to [-qmax, qmax] - only the quotient of the absmax element
-// can lie outside, by one rounding of s, so the caller sets it when that quotient does.
+// workgroup, almost never set) multiplies the weights by f1 * f2 first.
 template <int NV, bool WITH_P>
 __device__ __forceinline__ void k1_round_all(const float (&w)[4 * NV], float s, float rs, float qmaxf,
-                                             bool prescale, bool clamp, float f1, float f2, uint32_t (&code)[NV],
+                                             bool prescale, float f1, float f2, uint32_t (&code)[NV],
                                              uint32_t (&B)[4 * NV], int32_t& esum) {
   uint32_t biased = 0;
 #pragma unroll
@@ -392,17 +390,13 @@ __device__ __forceinline__ void k1_round_all(const float (&w)[4 * NV], float s, 
 #pragma unroll
       for (int e = 0; e < 4; ++e) wv[e] = wv[e] * f1 * f2;
     }
-    float xq[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) xq[e] = div_by_reciprocal(wv[e], s, rs);  // the IEEE quotient
-    if (clamp) {
-#pragma unroll
-      for (int e = 0; e < 4; ++e) xq[e] = __builtin_amdgcn_fmed3f(xq[e], -qmaxf, qmaxf);
-    }
     uint32_t tb[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const float xc = xq[e];
+      const float x = div_by_reciprocal(wv[e], s, rs);  // the IEEE quotient
+      // (leaving the clamp out for the channels that do not need it, as the 3x3 kernel does, was
+      // measured to cost more instructions here than the clamp itself)
+      const float xc = __builtin_amdgcn_fmed3f(x, -qmaxf, qmaxf);
       const float t = xc + kRoundMagic;  // round half to even; code + 128 in the low byte
       tb[e] = __float_as_uint(t);
       if (WITH_P) {
@@ -503,9 +497,8 @@ __device__ __forceinline__ void k1_channel(const LaunchArgs& a, const TensorDesc
     const float f1 = !prescale ? 1.0f : amax < 1.0f ? 0x1p64f : 0x1p-64f;
     const float a1 = amax * f1;
     const float f2 = !prescale ? 1.0f : a1 < 0x1p-60f ? 0x1p64f : a1 > 0x1p60f ? 0x1p-64f : 1.0f;
-    const float s2 = s * f1 * f2, rs2 = 1.0f / s2;
-    const bool clamp = prescale || !(div_by_reciprocal(amax * f1 * f2, s2, rs2) <= qmaxf);
-    k1_round_all<NV, kChannelStage>(w, s2, rs2, qmaxf, prescale, clamp, f1, f2, code, B, esum);
+    const float s2 = s * f1 * f2;
+    k1_round_all<NV, kChannelStage>(w, s2, 1.0f / s2, qmaxf, prescale, f1, f2, code, B, esum);
   }
 
   if (kChannelStage) {

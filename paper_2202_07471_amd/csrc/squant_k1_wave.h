@@ -91,9 +91,8 @@ __device__ __forceinline__ void k1_wave_channels(const LaunchArgs& a, const Tens
       const float f1 = !prescale ? 1.0f : amax < 1.0f ? 0x1p64f : 0x1p-64f;
       const float a1 = amax * f1;
       const float f2 = !prescale ? 1.0f : a1 < 0x1p-60f ? 0x1p64f : a1 > 0x1p60f ? 0x1p-64f : 1.0f;
-      const float s2 = s * f1 * f2, rs2 = 1.0f / s2;
-      const bool clamp = prescale || !(div_by_reciprocal(amax * f1 * f2, s2, rs2) <= qmaxf);
-      k1_round_all<NV, kChannelStage>(w, s2, rs2, qmaxf, prescale, clamp, f1, f2, code, B, esum);
+      const float s2 = s * f1 * f2;
+      k1_round_all<NV, kChannelStage>(w, s2, 1.0f / s2, qmaxf, prescale, f1, f2, code, B, esum);
     }
     // the weights are used up: the next channel's travel while this one's flips are chosen
     if (PREFETCH && m + 1 < c1) load_channel(m + 1, lane);
@@ -168,7 +167,8 @@ __device__ __forceinline__ void k1_wave_dispatch(const LaunchArgs& a, const Tens
 // One kernel per vector count.  The next channel's weights share the registers with the
 // current channel's perturbations and codes, about 9 per vector and 25 besides: two vectors fit
 // the 64 VGPRs of eight waves per SIMD, four the 80 of six, six the 96 of five, eight the 128 of
-// four.
+// four.  (Four vectors in 80 registers and six in 96 spill 12 and 32 bytes; the next step down
+// in waves was measured 2 to 4 points of the roofline slower.)
 template <int MODE, int NV>
 __global__ void __launch_bounds__(256)
     __attribute__((amdgpu_waves_per_eu(NV <= 2 ? 8 : NV <= 4 ? 6 : NV <= 6 ? 5 : 4)))
