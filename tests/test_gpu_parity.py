@@ -254,38 +254,20 @@ def test_config5_slice_batched(sq):
         assert_same(c, sc, w, 4, 2, what=f"config 5 tensor {s.index} {s.dist}")
 
 
-def test_config5_full_size_sampled(sq):
-    """All 256 tensors in one batched call (the benchmark's launch configuration); the
-    reference checks a sample of whole tensors and of single output channels."""
+def test_config5_full_size_every_tensor(sq):
+    """All 256 tensors in one batched call (the benchmark's launch configuration), and every one
+    of them compared with the reference in full (it takes the 604 M weights in a few seconds on
+    16 threads)."""
     specs = synth.config_specs(5)
     shape = specs[0].shape
-    dws = []
-    host_keep = {}
-    sample_tensors = {0, 129, 255}
-    rng = np.random.default_rng(1)
-    sample_channels = {int(t): sorted(set(int(c) for c in rng.integers(0, shape[0], 3)))
-                       for t in rng.choice(256, 40, replace=False)}
-    buf = np.empty(shape, np.float32)
-    for s in specs:
-        w = synth.generate(s, out=buf)
-        if s.index in sample_tensors:
-            host_keep[s.index] = w.copy()
-        elif s.index in sample_channels:
-            host_keep[s.index] = {c: w[c].copy() for c in sample_channels[s.index]}
-        dws.append(torch.from_numpy(w).cuda())
-    plan = sq.BatchPlan(dws)
+    host = [synth.generate(s) for s in specs]
+    plan = sq.BatchPlan([torch.from_numpy(w).cuda() for w in host])
     codes, scales = plan.run(4, 2)
     torch.cuda.synchronize()
-    for t in sample_tensors:
-        assert_same(codes[t], scales[t], host_keep[t], 4, 2, what=f"C5 full tensor {t}")
-    for t, chans in sample_channels.items():
-        if t in sample_tensors:
-            continue
-        for c in chans:
-            wc = host_keep[t][c][None]
-            want_c, want_s = oracle.quantize(wc, 4, 2)
-            assert np.array_equal(codes[t][c].cpu().numpy(), want_c[0]), f"C5 tensor {t} channel {c}"
-            assert scales[t][c].cpu().numpy().view(np.uint32) == want_s.view(np.uint32)[0]
+    for s in specs:
+        assert_same(codes[s.index], scales[s.index], host[s.index], 4, 2, threads=16, what=f"C5 tensor {s.index}")
+    host_keep = {t: host[t] for t in (0, 129, 255)}
+    sample_tensors = sorted(host_keep)
     # properties that hold at any size: codes in range, every scale positive
     for t in (7, 100, 200):
         assert int(codes[t].abs().max()) <= 7
